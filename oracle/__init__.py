@@ -1,0 +1,152 @@
+"""Python face of the CPU oracle (oracle/conv2d_oracle.c).
+
+TEST INFRASTRUCTURE ONLY: imported by tests, by the smoke check and by the
+benchmark's cpu_baseline leg.  The product package never imports this module,
+and this module never imports the product package.
+
+The oracle evaluates the layer's plain definition (Caffe convolution forward as
+kept by the paper, Sections 2 and 5) in FP64 over FP16 inputs; see the C file's
+header for the formula.  Here only: building/loading the shared object, argument
+marshalling, and the two things a comparison needs on top of the raw sums --
+the ReLU of the FP64 pre-activation and the tolerance
+|gpu - oracle| <= 4e-3 * sum|w*x| + 1e-3 stated for this build.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from typing import Optional, Sequence, Tuple
+
+import numpy as np
+
+_DIR = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_DIR, "conv2d_oracle.c")
+_LIB = os.path.join(_DIR, "libhgo.so")
+_lib = None
+
+REL_TOL = 4e-3
+ABS_TOL = 1e-3
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (-O2 -fopenmp).  Returns the library path."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-std=c11", "-o", _LIB, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        lib = ctypes.CDLL(_LIB)
+        u16p = ctypes.POINTER(ctypes.c_uint16)
+        i32p = ctypes.POINTER(ctypes.c_int32)
+        f64p = ctypes.POINTER(ctypes.c_double)
+        lib.hgo_half_to_double.argtypes = [ctypes.c_uint16]
+        lib.hgo_half_to_double.restype = ctypes.c_double
+        lib.hgo_conv2d_forward.argtypes = [i32p, u16p, u16p, u16p, f64p, f64p]
+        lib.hgo_conv2d_forward.restype = ctypes.c_int
+        lib.hgo_conv2d_points.argtypes = [i32p, u16p, u16p, u16p, ctypes.c_longlong, i32p, f64p, f64p]
+        lib.hgo_conv2d_points.restype = ctypes.c_int
+        lib.hgo_num_threads.restype = ctypes.c_int
+        lib.hgo_set_num_threads.argtypes = [ctypes.c_int]
+        _lib = lib
+    return _lib
+
+
+def _u16(a: Optional[np.ndarray]):
+    if a is None:
+        return None, ctypes.POINTER(ctypes.c_uint16)()
+    a = np.ascontiguousarray(a, dtype=np.float16)
+    return a, a.view(np.uint16).ctypes.data_as(ctypes.POINTER(ctypes.c_uint16))
+
+
+def _desc(desc: Sequence[int]):
+    d = np.asarray(desc, dtype=np.int32)
+    assert d.shape == (11,), "desc = (N,C,H,W,num_output,kernel,stride,pad,group,bias,relu)"
+    return d, d.ctypes.data_as(ctypes.POINTER(ctypes.c_int32))
+
+
+def out_shape(desc: Sequence[int]) -> Tuple[int, int, int, int]:
+    N, C, H, W, M, k, s, p = [int(v) for v in desc[:8]]
+    if s < 1 or k < 1 or H + 2 * p < k or W + 2 * p < k:
+        raise ValueError("descriptor has no output")
+    return (N, M, (H + 2 * p - k) // s + 1, (W + 2 * p - k) // s + 1)
+
+
+def half_to_double(bits: int) -> float:
+    return float(_load().hgo_half_to_double(int(bits)))
+
+
+def num_threads() -> int:
+    return int(_load().hgo_num_threads())
+
+
+def set_num_threads(n: int) -> None:
+    _load().hgo_set_num_threads(int(n))
+
+
+def conv2d_forward(desc, x, w, b=None):
+    """Full tensor: returns (pre, mag), FP64 arrays of shape [N][M][Ho][Wo].
+
+    pre = bias + sum of products (before ReLU); mag = sum of |products|.
+    """
+    lib = _load()
+    d, dp = _desc(desc)
+    xk, xp = _u16(x)
+    wk, wp = _u16(w)
+    bk, bp = _u16(b if d[9] else None)
+    if d[9] and b is None:
+        raise ValueError("bias=1 needs b")
+    shape = out_shape(d)
+    pre = np.empty(shape, dtype=np.float64)
+    mag = np.empty(shape, dtype=np.float64)
+    f64p = ctypes.POINTER(ctypes.c_double)
+    rc = lib.hgo_conv2d_forward(dp, xp, wp, bp, pre.ctypes.data_as(f64p), mag.ctypes.data_as(f64p))
+    if rc:
+        raise ValueError(f"oracle rejected the descriptor (rc={rc})")
+    return pre, mag
+
+
+def conv2d_points(desc, x, w, b, idx):
+    """Selected outputs: idx is an int array [npts][4] of (n, m, oh, ow). Returns (pre, mag)."""
+    lib = _load()
+    d, dp = _desc(desc)
+    xk, xp = _u16(x)
+    wk, wp = _u16(w)
+    bk, bp = _u16(b if d[9] else None)
+    idx = np.ascontiguousarray(idx, dtype=np.int32).reshape(-1, 4)
+    n = idx.shape[0]
+    pre = np.empty(n, dtype=np.float64)
+    mag = np.empty(n, dtype=np.float64)
+    f64p = ctypes.POINTER(ctypes.c_double)
+    rc = lib.hgo_conv2d_points(dp, xp, wp, bp, n, idx.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)),
+                               pre.ctypes.data_as(f64p), mag.ctypes.data_as(f64p))
+    if rc:
+        raise ValueError(f"oracle rejected the request (rc={rc})")
+    return pre, mag
+
+
+def reference(pre: np.ndarray, mag: np.ndarray, relu: int):
+    """(ref, bound): the FP64 expected output and the allowed absolute deviation.
+
+    The bound is formed from the pre-ReLU taps only (the bias is not part of
+    sum|w*x|); ReLU is 1-Lipschitz, so the same bound holds after it.
+    """
+    ref = np.maximum(pre, 0.0) if relu else pre
+    return ref, REL_TOL * mag + ABS_TOL
+
+
+def check(y, pre, mag, relu):
+    """Compare an FP16 result with the oracle. Returns (ok, worst ratio |err|/bound, index)."""
+    ref, bound = reference(pre, mag, relu)
+    yd = np.asarray(y).astype(np.float64).reshape(ref.shape)
+    err = np.abs(yd - ref)
+    bad = ~np.isfinite(yd)
+    ratio = np.where(bad, np.inf, err / bound)
+    worst = int(np.argmax(ratio))
+    r = float(ratio.reshape(-1)[worst])
+    return bool(r <= 1.0), r, np.unravel_index(worst, ref.shape)
