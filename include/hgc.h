@@ -1,0 +1,140 @@
+/*
+ * hgc -- FP16 convolution-layer forward pass for AMD MI355X (gfx950), C ABI.
+ *
+ * The operation is the convolution layer the paper's engine inherits from BVLC
+ * Caffe (Section 2 "Modified from Caffe"; Section 5: same layers, same weight
+ * layout), run in half precision on the GPU (Section 1, feature "half precision
+ * for all layers"), forward only (feature "forward only mode"):
+ *
+ *   y[n][m][oh][ow] = act( b[m] + sum_{c<C/group, r<kernel, q<kernel}
+ *        w[m][c][r][q] * x[n][g*(C/group) + c][oh*stride - pad + r][ow*stride - pad + q] )
+ *
+ *   g  = m / (num_output/group)            group of output channel m
+ *   Ho = floor((H + 2*pad - kernel)/stride) + 1,  Wo likewise
+ *   taps outside the image contribute zero; act = max(.,0) if relu else identity.
+ *
+ * It is a cross-correlation (no kernel flip).  Products are FP16 x FP16, sums are
+ * kept in FP32 (Section 3.1: overflow and underflow arise during accumulation),
+ * and the result is rounded to FP16 once, at the store.
+ *
+ * Boundary rules taken from the paper:
+ *   - scalars are ordinary host scalars, tensors are half: the descriptor holds
+ *     int32 values in host memory, callers never convert them (Section 3.2);
+ *   - tensors, weights included, arrive in FP16 and are used as they are: there
+ *     is no float<->half conversion on the path (Section 3.3).
+ *
+ * All tensors are dense, row-major FP16 in DEVICE memory of the GPU the stream
+ * belongs to:  x[N][C][H][W], w[num_output][C/group][kernel][kernel],
+ * b[num_output], y[N][num_output][Ho][Wo].  Base pointers need 2-byte alignment
+ * only; 16-byte aligned bases (any allocator gives them) enable the fast paths.
+ *
+ * Ownership: the caller owns every buffer.  The library never allocates, frees,
+ * copies to the host or synchronises; each call only enqueues kernels on
+ * `stream` and returns.  x, w, b are read-only; every element of y is written
+ * exactly once; y must not overlap x, w, b or the workspace.  The descriptor is
+ * read during the call only.  Calls are thread-safe.
+ */
+#ifndef HGC_H
+#define HGC_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct hgc_conv2d_desc {
+    int32_t N, C, H, W;     /* input x: [N][C][H][W]                                   */
+    int32_t num_output;     /* M; w: [M][C/group][kernel][kernel]                      */
+    int32_t kernel;         /* square kernel extent, >= 1                              */
+    int32_t stride;         /* >= 1, both axes                                         */
+    int32_t pad;            /* >= 0, zeros, symmetric, both axes                       */
+    int32_t group;          /* >= 1; C % group == 0 and num_output % group == 0        */
+    int32_t bias;           /* 0 or 1; b may be NULL iff 0                             */
+    int32_t relu;           /* 0 or 1; fused max(.,0) after the bias                   */
+} hgc_conv2d_desc;
+
+typedef int32_t hgc_status;
+#define HGC_OK              0
+#define HGC_ERR_NULL       (-1)  /* a required pointer is NULL                          */
+#define HGC_ERR_BAD_DESC   (-2)  /* a field out of range, or the output would be empty  */
+#define HGC_ERR_TOO_LARGE  (-3)  /* a tensor has more than 2^31 - 1 elements            */
+#define HGC_ERR_WORKSPACE  (-4)  /* workspace NULL or smaller than required             */
+#define HGC_ERR_LAUNCH     (-5)  /* the HIP runtime refused a launch                    */
+
+/* Algorithms (hgc_plan.path). */
+#define HGC_PATH_AUTO       0    /* only as an argument of hgc_set_forced_path          */
+#define HGC_PATH_DIRECT     1    /* one thread per output, FP32 FMA; any descriptor     */
+#define HGC_PATH_IGEMM      2    /* implicit GEMM on FP16 MFMA, input halo tile in LDS  */
+#define HGC_PATH_IGEMM_SPLITK 3  /* the same with the reduction split over workgroups;
+                                    FP32 partial sums in the workspace + a reduce kernel */
+#define HGC_PATH_DEPTHWISE  4    /* group == C == num_output streaming kernel           */
+
+/* What a call will do for a descriptor; filled by hgc_conv2d_plan. */
+typedef struct hgc_plan {
+    int32_t path;            /* HGC_PATH_*                                              */
+    int32_t Ho, Wo;          /* output extent                                           */
+    int32_t tile_m;          /* output channels per workgroup                           */
+    int32_t tile_h, tile_w;  /* output pixels per workgroup: tile_h rows x tile_w cols  */
+    int32_t split_k;         /* >= 1; number of reduction slices                        */
+    int32_t variant;         /* kernel instantiation index (diagnostic)                 */
+    int32_t grid;            /* workgroups of the main kernel                           */
+    int32_t block;           /* threads per workgroup                                   */
+    int64_t workspace_bytes; /* scratch the path needs (0 unless split_k > 1)           */
+    int64_t lds_bytes;       /* LDS per workgroup                                       */
+} hgc_plan;
+
+/*
+ * Convolution forward, workspace-free algorithms only (operation: header comment).
+ * desc: host. x, w, b, y: device. stream: a hipStream_t (NULL = default stream).
+ * Errors, checked in this order and before any GPU work: HGC_ERR_NULL (desc, x, w
+ * or y NULL; b NULL with bias = 1), HGC_ERR_BAD_DESC, HGC_ERR_TOO_LARGE; then
+ * HGC_ERR_LAUNCH if the runtime rejects a launch.  On error nothing is enqueued.
+ */
+hgc_status hgc_conv2d_forward(const hgc_conv2d_desc *desc, const void *x, const void *w,
+                              const void *b, void *y, void *stream);
+
+/*
+ * The same operation with a caller-owned device scratch buffer, which allows the
+ * split-reduction algorithm for layers with few output pixels (the accumulation
+ * stays in FP32 across slices, Section 3.1).  workspace_bytes must be at least
+ * what hgc_conv2d_workspace_size reports (else HGC_ERR_WORKSPACE, checked after
+ * the descriptor); workspace may be NULL when that is 0.  The workspace content
+ * is undefined afterwards.  Results are deterministic for a given descriptor.
+ */
+hgc_status hgc_conv2d_forward_ws(const hgc_conv2d_desc *desc, const void *x, const void *w,
+                                 const void *b, void *y, void *workspace,
+                                 size_t workspace_bytes, void *stream);
+
+/*
+ * Scratch bytes hgc_conv2d_forward_ws wants for this descriptor (may be 0).
+ * Host-only: touches no GPU.  Errors: HGC_ERR_NULL, HGC_ERR_BAD_DESC, HGC_ERR_TOO_LARGE.
+ */
+hgc_status hgc_conv2d_workspace_size(const hgc_conv2d_desc *desc, size_t *bytes_out);
+
+/*
+ * The algorithm and launch shape a call would use.  with_workspace = 0 describes
+ * hgc_conv2d_forward, 1 describes hgc_conv2d_forward_ws.  Host-only.
+ */
+hgc_status hgc_conv2d_plan(const hgc_conv2d_desc *desc, int32_t with_workspace, hgc_plan *plan_out);
+
+/*
+ * Test/diagnostic control: force one algorithm (HGC_PATH_*) for every later call
+ * in this process where it applies, or HGC_PATH_AUTO to restore the heuristic.
+ * A forced path that cannot run a descriptor falls back to HGC_PATH_DIRECT.
+ * tile_variant >= 0 additionally forces the implicit-GEMM instantiation; -1 = automatic.
+ * Returns the previous forced path.
+ */
+int32_t hgc_set_forced_path(int32_t path, int32_t tile_variant);
+
+/* Static, NUL-terminated description of a status code. */
+const char *hgc_status_string(hgc_status status);
+
+/* Library version: major * 10000 + minor * 100 + patch. */
+int32_t hgc_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HGC_H */

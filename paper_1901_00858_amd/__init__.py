@@ -1,0 +1,13 @@
+"""FP16 convolution-layer forward for MI355X: thin Python binding of libhgc.
+
+The package holds the HIP sources (csrc/), the build step (build.py) and a
+ctypes binding (binding.py) whose functions carry the C ABI's names and only
+marshal arguments.  Every step of the computation runs in the HIP kernels;
+there is no CPU fallback: loading fails loudly when libhgc.so is missing.
+"""
+from .binding import (  # noqa: F401
+    ConvDesc, Plan, HgcError, PATH_AUTO, PATH_DIRECT, PATH_IGEMM, PATH_IGEMM_SPLITK,
+    PATH_DEPTHWISE, PATH_NAMES, load, library_path, conv2d_forward, conv2d_forward_ws,
+    conv2d_workspace_size, conv2d_plan, set_forced_path, status_string, version,
+    forward_raw, forward_ws_raw,
+)

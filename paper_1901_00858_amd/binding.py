@@ -1,0 +1,182 @@
+"""ctypes binding of include/hgc.h.  Argument marshalling only.
+
+Tensors are torch CUDA tensors (torch is used for device memory and streams and
+for nothing else); the functions pass their data pointers and the current
+stream's handle to the C entry points of the same name.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Sequence
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_PKG, "libhgc.so")
+_lib = None
+
+PATH_AUTO, PATH_DIRECT, PATH_IGEMM, PATH_IGEMM_SPLITK, PATH_DEPTHWISE = 0, 1, 2, 3, 4
+PATH_NAMES = {1: "direct", 2: "igemm", 3: "igemm_splitk", 4: "depthwise"}
+
+
+class HgcError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {status_string(status)} (status {status})")
+
+
+class ConvDesc(ctypes.Structure):
+    """hgc_conv2d_desc: eleven int32 fields in host memory."""
+    _fields_ = [(n, ctypes.c_int32) for n in
+                ("N", "C", "H", "W", "num_output", "kernel", "stride", "pad", "group", "bias", "relu")]
+
+    @classmethod
+    def make(cls, desc) -> "ConvDesc":
+        if isinstance(desc, cls):
+            return desc
+        if hasattr(desc, "desc"):
+            desc = desc.desc()
+        vals = [int(v) for v in desc]
+        if len(vals) != 11:
+            raise ValueError("desc = (N,C,H,W,num_output,kernel,stride,pad,group,bias,relu)")
+        return cls(*vals)
+
+    def out_shape(self):
+        ho = (self.H + 2 * self.pad - self.kernel) // self.stride + 1
+        wo = (self.W + 2 * self.pad - self.kernel) // self.stride + 1
+        return (self.N, self.num_output, ho, wo)
+
+
+class Plan(ctypes.Structure):
+    """hgc_plan."""
+    _fields_ = [(n, ctypes.c_int32) for n in
+                ("path", "Ho", "Wo", "tile_m", "tile_h", "tile_w", "split_k", "variant", "grid", "block")] + \
+               [("workspace_bytes", ctypes.c_int64), ("lds_bytes", ctypes.c_int64)]
+
+    def as_dict(self):
+        d = {n: int(getattr(self, n)) for n, _ in self._fields_}
+        d["path_name"] = PATH_NAMES.get(d["path"], "?")
+        return d
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def load():
+    """Load libhgc.so. Raises if it has not been built (no fallback exists)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise ImportError(
+            f"{_LIB_PATH} is missing: build it with `python -m paper_1901_00858_amd.build` "
+            "(or __graft_entry__.build()); there is no fallback implementation")
+    lib = ctypes.CDLL(_LIB_PATH)
+    vp, dp = ctypes.c_void_p, ctypes.POINTER(ConvDesc)
+    lib.hgc_conv2d_forward.argtypes = [dp, vp, vp, vp, vp, vp]
+    lib.hgc_conv2d_forward.restype = ctypes.c_int32
+    lib.hgc_conv2d_forward_ws.argtypes = [dp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
+    lib.hgc_conv2d_forward_ws.restype = ctypes.c_int32
+    lib.hgc_conv2d_workspace_size.argtypes = [dp, ctypes.POINTER(ctypes.c_size_t)]
+    lib.hgc_conv2d_workspace_size.restype = ctypes.c_int32
+    lib.hgc_conv2d_plan.argtypes = [dp, ctypes.c_int32, ctypes.POINTER(Plan)]
+    lib.hgc_conv2d_plan.restype = ctypes.c_int32
+    lib.hgc_set_forced_path.argtypes = [ctypes.c_int32, ctypes.c_int32]
+    lib.hgc_set_forced_path.restype = ctypes.c_int32
+    lib.hgc_status_string.argtypes = [ctypes.c_int32]
+    lib.hgc_status_string.restype = ctypes.c_char_p
+    lib.hgc_version.restype = ctypes.c_int32
+    _lib = lib
+    return lib
+
+
+def status_string(status: int) -> str:
+    return load().hgc_status_string(int(status)).decode()
+
+
+def version() -> int:
+    return int(load().hgc_version())
+
+
+def set_forced_path(path: int = PATH_AUTO, tile_variant: int = -1) -> int:
+    return int(load().hgc_set_forced_path(int(path), int(tile_variant)))
+
+
+def conv2d_workspace_size(desc) -> int:
+    d = ConvDesc.make(desc)
+    n = ctypes.c_size_t(0)
+    st = load().hgc_conv2d_workspace_size(ctypes.byref(d), ctypes.byref(n))
+    if st != 0:
+        raise HgcError(st, "hgc_conv2d_workspace_size")
+    return int(n.value)
+
+
+def conv2d_plan(desc, with_workspace: bool = False) -> Plan:
+    d = ConvDesc.make(desc)
+    p = Plan()
+    st = load().hgc_conv2d_plan(ctypes.byref(d), 1 if with_workspace else 0, ctypes.byref(p))
+    if st != 0:
+        raise HgcError(st, "hgc_conv2d_plan")
+    return p
+
+
+def forward_raw(desc: Optional[ConvDesc], x: int, w: int, b: int, y: int, stream: int = 0) -> int:
+    """hgc_conv2d_forward on raw addresses; returns the status (no exception)."""
+    dref = ctypes.byref(desc) if desc is not None else None
+    return int(load().hgc_conv2d_forward(dref, x or None, w or None, b or None, y or None, stream or None))
+
+
+def forward_ws_raw(desc: Optional[ConvDesc], x: int, w: int, b: int, y: int, ws: int, ws_bytes: int,
+                   stream: int = 0) -> int:
+    dref = ctypes.byref(desc) if desc is not None else None
+    return int(load().hgc_conv2d_forward_ws(dref, x or None, w or None, b or None, y or None,
+                                            ws or None, int(ws_bytes), stream or None))
+
+
+def _check_tensor(t, name, shape=None):
+    import torch
+    if not isinstance(t, torch.Tensor) or not t.is_cuda or t.dtype != torch.float16 or not t.is_contiguous():
+        raise TypeError(f"{name} must be a contiguous float16 CUDA tensor")
+    if shape is not None and tuple(t.shape) != tuple(shape):
+        raise ValueError(f"{name} has shape {tuple(t.shape)}, expected {tuple(shape)}")
+
+
+def _marshal(desc, x, w, b, y):
+    import torch
+    d = ConvDesc.make(desc)
+    cg = d.C // d.group if d.group > 0 and d.C % d.group == 0 else None
+    _check_tensor(x, "x", (d.N, d.C, d.H, d.W))
+    _check_tensor(w, "w", (d.num_output, cg, d.kernel, d.kernel) if cg else None)
+    if d.bias:
+        if b is None:
+            raise ValueError("bias=1 needs b")
+        _check_tensor(b, "b", (d.num_output,))
+    if y is None:
+        y = torch.empty(d.out_shape(), dtype=torch.float16, device=x.device)
+    else:
+        _check_tensor(y, "y", d.out_shape())
+    stream = torch.cuda.current_stream(x.device).cuda_stream
+    return d, y, stream
+
+
+def conv2d_forward(desc, x, w, b=None, y=None):
+    """hgc_conv2d_forward on torch tensors, on torch's current stream. Returns y."""
+    d, y, stream = _marshal(desc, x, w, b, y)
+    st = forward_raw(d, x.data_ptr(), w.data_ptr(), b.data_ptr() if (d.bias and b is not None) else 0,
+                     y.data_ptr(), stream)
+    if st != 0:
+        raise HgcError(st, "hgc_conv2d_forward")
+    return y
+
+
+def conv2d_forward_ws(desc, x, w, b=None, y=None, workspace=None):
+    """hgc_conv2d_forward_ws; `workspace` is a CUDA uint8 tensor (or None when 0 bytes are needed)."""
+    d, y, stream = _marshal(desc, x, w, b, y)
+    ws_ptr, ws_bytes = 0, 0
+    if workspace is not None:
+        ws_ptr, ws_bytes = workspace.data_ptr(), workspace.numel() * workspace.element_size()
+    st = forward_ws_raw(d, x.data_ptr(), w.data_ptr(), b.data_ptr() if (d.bias and b is not None) else 0,
+                        y.data_ptr(), ws_ptr, ws_bytes, stream)
+    if st != 0:
+        raise HgcError(st, "hgc_conv2d_forward_ws")
+    return y

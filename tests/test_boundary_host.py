@@ -1,0 +1,162 @@
+"""Host-only tests of the C ABI: exported symbols, validation order, planning.
+
+None of these touches a GPU: every error status is returned before any HIP call,
+and the plan / workspace queries are plain host arithmetic.
+"""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_1901_00858_amd as hgc
+from paper_1901_00858_amd import ConvDesc
+from workloads import CONFIGS, ConvLayer
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+FAKE = 0x1000  # a non-NULL address that is never dereferenced on the paths tested here
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(hgc.library_path()):
+        from paper_1901_00858_amd.build import build_library
+        build_library()
+    return hgc.load()
+
+
+def test_every_declared_symbol_is_exported(lib):
+    with open(os.path.join(ROOT, "include", "hgc.h")) as f:
+        text = f.read()
+    names = set(re.findall(r"\b(hgc_[a-z0-9_]+)\s*\(", text))
+    assert {"hgc_conv2d_forward", "hgc_conv2d_forward_ws", "hgc_conv2d_workspace_size",
+            "hgc_conv2d_plan", "hgc_set_forced_path", "hgc_status_string", "hgc_version"} <= names
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def test_struct_layouts_match_header(lib):
+    assert ctypes.sizeof(ConvDesc) == 44
+    assert ctypes.sizeof(hgc.Plan) == 56
+
+
+GOOD = (1, 4, 8, 8, 4, 3, 1, 1, 1, 1, 1)
+
+
+def _d(**kw):
+    names = ("N", "C", "H", "W", "num_output", "kernel", "stride", "pad", "group", "bias", "relu")
+    v = dict(zip(names, GOOD)); v.update(kw)
+    return ConvDesc(*[v[n] for n in names])
+
+
+def test_null_pointers_come_first(lib):
+    d = _d()
+    assert hgc.forward_raw(None, FAKE, FAKE, FAKE, FAKE) == -1
+    assert hgc.forward_raw(d, 0, FAKE, FAKE, FAKE) == -1
+    assert hgc.forward_raw(d, FAKE, 0, FAKE, FAKE) == -1
+    assert hgc.forward_raw(d, FAKE, FAKE, FAKE, 0) == -1
+    assert hgc.forward_raw(d, FAKE, FAKE, 0, FAKE) == -1          # bias=1 needs b
+    # NULL wins over a bad descriptor
+    assert hgc.forward_raw(_d(stride=0), 0, FAKE, FAKE, FAKE) == -1
+    n = ctypes.c_size_t()
+    assert lib.hgc_conv2d_workspace_size(None, ctypes.byref(n)) == -1
+    assert lib.hgc_conv2d_workspace_size(ctypes.byref(d), None) == -1
+    assert lib.hgc_conv2d_plan(ctypes.byref(d), 0, None) == -1
+
+
+@pytest.mark.parametrize("kw", [
+    dict(N=0), dict(C=0), dict(H=0), dict(W=-1), dict(num_output=0), dict(kernel=0), dict(stride=0),
+    dict(pad=-1), dict(group=0), dict(group=3), dict(C=6, group=3, num_output=4),
+    dict(bias=2), dict(relu=-1), dict(kernel=11), dict(H=2, W=9, kernel=5, pad=1),
+])
+def test_bad_descriptors(lib, kw):
+    d = _d(**kw)
+    assert hgc.forward_raw(d, FAKE, FAKE, FAKE, FAKE) == -2
+    assert hgc.forward_ws_raw(d, FAKE, FAKE, FAKE, FAKE, FAKE, 1 << 30) == -2
+    n = ctypes.c_size_t()
+    assert lib.hgc_conv2d_workspace_size(ctypes.byref(d), ctypes.byref(n)) == -2
+    with pytest.raises(hgc.HgcError):
+        hgc.conv2d_plan(d)
+
+
+def test_too_large(lib):
+    assert hgc.forward_raw(_d(N=70000, C=64, H=224, W=224), FAKE, FAKE, FAKE, FAKE) == -3
+    assert hgc.forward_raw(_d(num_output=4 << 20, C=1024, group=1), FAKE, FAKE, FAKE, FAKE) == -3
+    assert hgc.forward_raw(_d(N=4096, num_output=4096, H=64, W=64, C=4), FAKE, FAKE, FAKE, FAKE) == -3
+
+
+def test_workspace_is_checked_before_any_launch(lib):
+    L = ConvLayer("small_p", 1, 512, 14, 14, 512, 3, 1, 1)
+    need = hgc.conv2d_workspace_size(L)
+    plan = hgc.conv2d_plan(L, with_workspace=True)
+    assert plan.path == hgc.PATH_IGEMM_SPLITK and plan.split_k > 1
+    assert need >= plan.workspace_bytes == 4 * plan.split_k * 512 * 14 * 14
+    d = ConvDesc.make(L)
+    assert hgc.forward_ws_raw(d, FAKE, FAKE, FAKE, FAKE, 0, 0) == -4
+    assert hgc.forward_ws_raw(d, FAKE, FAKE, FAKE, FAKE, FAKE, need - 1) == -4
+    # the workspace-free entry never needs one
+    assert hgc.conv2d_plan(L, with_workspace=False).workspace_bytes == 0
+
+
+def test_status_strings(lib):
+    seen = {hgc.status_string(s) for s in (0, -1, -2, -3, -4, -5)}
+    assert len(seen) == 6 and hgc.status_string(0) == "ok"
+    assert hgc.status_string(-99) == "unknown status"
+    assert hgc.version() >= 100
+
+
+def test_plans_for_every_benchmark_layer(lib):
+    for name, fn in CONFIGS.items():
+        for N in (1, 16):
+            for L in fn(N):
+                for ws in (False, True):
+                    p = hgc.conv2d_plan(L, ws)
+                    assert (p.Ho, p.Wo) == (L.Ho, L.Wo)
+                    assert p.path in hgc.PATH_NAMES and p.grid >= 1 and p.block == 256
+                    assert p.lds_bytes <= 160 * 1024
+                    if p.path in (hgc.PATH_IGEMM, hgc.PATH_IGEMM_SPLITK):
+                        assert p.tile_h * p.tile_w in (128, 256, 512) and p.tile_m in (32, 64, 128, 256)
+                    if not ws:
+                        assert p.workspace_bytes == 0 and p.split_k == 1
+                    else:
+                        assert hgc.conv2d_workspace_size(L) >= p.workspace_bytes
+                    if L.G == L.C == L.M and L.k == 3:
+                        assert p.path == hgc.PATH_DEPTHWISE
+
+
+def test_forced_path_round_trip(lib):
+    L = ConvLayer("f", 1, 64, 56, 56, 64, 3, 1, 1)
+    try:
+        assert hgc.set_forced_path(hgc.PATH_DIRECT) == hgc.PATH_AUTO
+        assert hgc.conv2d_plan(L).path == hgc.PATH_DIRECT
+        assert hgc.set_forced_path(hgc.PATH_IGEMM) == hgc.PATH_DIRECT
+        assert hgc.conv2d_plan(L, True).path == hgc.PATH_IGEMM
+        hgc.set_forced_path(hgc.PATH_DEPTHWISE)          # not applicable -> direct
+        assert hgc.conv2d_plan(L).path == hgc.PATH_DIRECT
+        hgc.set_forced_path(hgc.PATH_IGEMM, 9999)        # no such instantiation -> direct
+        assert hgc.conv2d_plan(L).path == hgc.PATH_DIRECT
+    finally:
+        hgc.set_forced_path(hgc.PATH_AUTO)
+    assert hgc.conv2d_plan(L).path == hgc.PATH_IGEMM
+
+
+def test_binding_refuses_cpu_tensors(lib):
+    torch = pytest.importorskip("torch")
+    L = ConvLayer("c", 1, 4, 8, 8, 4, 3, 1, 1)
+    x = torch.zeros(L.x_shape, dtype=torch.float16)
+    w = torch.zeros(L.w_shape, dtype=torch.float16)
+    b = torch.zeros(L.M, dtype=torch.float16)
+    with pytest.raises(TypeError):
+        hgc.conv2d_forward(L, x, w, b)
+
+
+def test_product_package_does_not_import_the_oracle():
+    pkg = os.path.join(ROOT, "paper_1901_00858_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".h", ".cpp")):
+                with open(os.path.join(dirpath, f)) as fh:
+                    text = fh.read()
+                assert "oracle" not in text.lower(), f
+    with open(os.path.join(ROOT, "oracle", "__init__.py")) as fh:
+        assert "paper_1901_00858_amd" not in fh.read().replace("never imports the product package", "")

@@ -1,0 +1,184 @@
+"""GPU parity: the HIP path, called through the C ABI, against the FP64 oracle.
+
+Tolerance (stated for this build): |gpu - oracle| <= 4e-3 * sum|w*x| + 1e-3, the sum
+taken over the taps before the bias and ReLU; integer-valued inputs must match exactly.
+"""
+import numpy as np
+import pytest
+
+import paper_1901_00858_amd as hgc
+from workloads import CONFIGS, ConvLayer, layer_seed, make_integer_tensors, make_tensors
+
+from gpu_helpers import assert_full, assert_points, run_layer, sample_points, say
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _gpu():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    hgc.load()
+    hgc.set_forced_path(hgc.PATH_AUTO)
+    yield
+    hgc.set_forced_path(hgc.PATH_AUTO)
+
+
+#          N  C   H   W   M  k  s  p  G
+SHAPES = [
+    (1, 3, 32, 32, 16, 3, 1, 1, 1),      # config 1
+    (2, 16, 20, 24, 32, 3, 1, 1, 1),     # aligned channels, even W
+    (2, 16, 21, 23, 32, 3, 1, 1, 1),     # odd W: 2-byte input loads
+    (1, 24, 17, 18, 40, 3, 1, 1, 1),     # Cg % 16 != 0, ragged channel tile
+    (1, 20, 17, 18, 72, 3, 1, 1, 1),     # Cg % 8 != 0: scalar weight loads
+    (3, 32, 15, 15, 64, 3, 2, 1, 1),     # stride 2, odd W
+    (2, 32, 28, 28, 64, 3, 2, 1, 1),     # stride 2, even W, floor drops a padded row
+    (1, 64, 9, 40, 160, 3, 1, 0, 1),     # pad 0, wide, M ragged against 128 (two tiles)
+    (2, 64, 14, 14, 96, 3, 1, 1, 2),     # groups
+    (1, 48, 13, 13, 48, 3, 1, 1, 3),     # groups, odd W
+    (2, 64, 12, 12, 64, 1, 1, 0, 1),     # pointwise
+    (1, 200, 7, 7, 96, 1, 1, 0, 1),      # pointwise, odd W, Cg % 64 != 0
+    (1, 36, 10, 10, 48, 1, 1, 0, 1),     # pointwise, Cg % 8 != 0
+    (2, 32, 16, 16, 32, 1, 2, 0, 1),     # pointwise, stride 2
+    (1, 96, 27, 27, 64, 5, 1, 2, 2),     # 5x5 grouped (AlexNet conv2 style), odd W
+    (1, 16, 20, 20, 32, 5, 2, 2, 1),     # 5x5 stride 2
+    (1, 3, 40, 40, 32, 7, 2, 3, 1),      # stem style
+    (1, 3, 37, 37, 24, 7, 2, 3, 1),      # stem style, odd W, ragged M
+    (1, 3, 43, 43, 24, 11, 4, 0, 1),     # AlexNet conv1 style -> direct path
+    (1, 8, 12, 12, 16, 2, 2, 0, 1),      # even kernel -> direct path
+    (2, 24, 19, 19, 24, 3, 1, 1, 24),    # depthwise
+    (1, 16, 30, 30, 16, 3, 2, 1, 16),    # depthwise stride 2
+    (1, 8, 16, 16, 8, 5, 1, 2, 8),       # depthwise 5x5
+    (1, 8, 9, 9, 16, 3, 1, 1, 8),        # channel multiplier 2 (Mg = 2) -> direct
+    (1, 16, 33, 70, 32, 3, 1, 1, 1),     # several window tiles in both directions
+    (1, 16, 3, 3, 32, 3, 1, 0, 1),       # single output pixel
+]
+
+
+def _layer(t, bias=1, relu=1):
+    N, C, H, W, M, k, s, p, G = t
+    return ConvLayer("case", N, C, H, W, M, k, s, p, G, bias, relu)
+
+
+@pytest.mark.parametrize("t", SHAPES)
+def test_shapes_full_tensor(oracle, t):
+    for bias, relu, ws in [(1, 1, False), (0, 0, True)]:
+        L = _layer(t, bias, relu)
+        say(f"[case] {L} ws={ws} plan={hgc.conv2d_plan(L, ws).as_dict()}")
+        x, w, b = make_tensors(L, seed=100 + bias)
+        y = run_layer(L, x, w, b, use_ws=ws)
+        assert_full(oracle, L, x, w, b, y)
+
+
+@pytest.mark.parametrize("t", SHAPES)
+def test_integer_inputs_are_exact(oracle, t):
+    L = _layer(t, 1, 0)
+    if L.Kg * 8 + 8 > 2048:
+        x, w, b = make_integer_tensors(L, seed=7, xmax=1, wmax=1)
+        if L.Kg + 8 > 2048:
+            pytest.skip("sums leave the exact range")
+    else:
+        x, w, b = make_integer_tensors(L, seed=7)
+    for ws in (False, True):
+        say(f"[int] {L} ws={ws}")
+        y = run_layer(L, x, w, b, use_ws=ws)
+        pre, _ = oracle.conv2d_forward(L.desc(), x, w, b)
+        assert np.array_equal(y.astype(np.float64), pre), f"{L} ws={ws}"
+
+
+def test_every_tile_variant_agrees_with_the_oracle(oracle):
+    """Force each implicit-GEMM instantiation on a shape it accepts."""
+    import ctypes
+    probes = {1: (2, 64, 18, 20, 160, 1, 1, 0, 1), 3: (2, 32, 18, 20, 160, 3, 1, 1, 1),
+              5: (1, 16, 18, 20, 96, 5, 1, 2, 1), 7: (1, 8, 18, 20, 48, 7, 1, 3, 1)}
+    seen = 0
+    try:
+        for v in range(64):
+            for k, t in probes.items():
+                L = _layer(t)
+                hgc.set_forced_path(hgc.PATH_IGEMM, v)
+                p = hgc.conv2d_plan(L, False)
+                if p.path != hgc.PATH_IGEMM or p.variant != v:
+                    continue
+                seen += 1
+                for ws in (False, True):
+                    hgc.set_forced_path(hgc.PATH_IGEMM_SPLITK if ws else hgc.PATH_IGEMM, v)
+                    say(f"[variant {v}] {L} ws={ws} plan={hgc.conv2d_plan(L, ws).as_dict()}")
+                    x, w, b = make_tensors(L, seed=v)
+                    y = run_layer(L, x, w, b, use_ws=ws)
+                    assert_full(oracle, L, x, w, b, y, tag=f"variant {v}")
+    finally:
+        hgc.set_forced_path(hgc.PATH_AUTO)
+    assert seen >= 12
+
+
+def test_direct_and_mfma_paths_agree(oracle):
+    L = _layer((2, 32, 20, 22, 64, 3, 1, 1, 1))
+    x, w, b = make_tensors(L, seed=1)
+    try:
+        hgc.set_forced_path(hgc.PATH_DIRECT)
+        yd = run_layer(L, x, w, b)
+        hgc.set_forced_path(hgc.PATH_IGEMM)
+        ym = run_layer(L, x, w, b)
+    finally:
+        hgc.set_forced_path(hgc.PATH_AUTO)
+    assert_full(oracle, L, x, w, b, yd, "direct")
+    assert_full(oracle, L, x, w, b, ym, "igemm")
+    # same call twice: bit-identical (no order-dependent accumulation)
+    assert np.array_equal(run_layer(L, x, w, b, use_ws=True).view(np.uint16),
+                          run_layer(L, x, w, b, use_ws=True).view(np.uint16))
+
+
+def test_unaligned_base_pointers_fall_back(oracle):
+    """Tensors that start 2 bytes into an allocation: vector loads are not allowed."""
+    import torch
+    L = _layer((1, 16, 12, 12, 32, 3, 1, 1, 1))
+    x, w, b = make_tensors(L, seed=3)
+
+    def shifted(a):
+        buf = torch.zeros(a.size + 1, dtype=torch.float16, device="cuda")
+        buf[1:] = torch.from_numpy(a.reshape(-1)).cuda()
+        return buf, buf[1:].view(a.shape)
+
+    xb, xs = shifted(x); wb, wsft = shifted(w); bb, bs = shifted(b)
+    y = torch.empty(L.y_shape, dtype=torch.float16, device="cuda")
+    d = hgc.ConvDesc.make(L)
+    st = hgc.forward_raw(d, xs.data_ptr(), wsft.data_ptr(), bs.data_ptr(), y.data_ptr(),
+                         torch.cuda.current_stream().cuda_stream)
+    assert st == 0
+    torch.cuda.synchronize()
+    assert_full(oracle, L, x, w, b, y.cpu().numpy(), "unaligned")
+
+
+@pytest.mark.parametrize("cfg", ["cfg1", "alexnet", "vgg16", "resnet50", "mobilenet_v1"])
+def test_configs_batch1_full_tensor(oracle, cfg):
+    worst = 0.0
+    for i, L in enumerate(CONFIGS[cfg](1)):
+        x, w, b = make_tensors(L, seed=layer_seed(cfg, i))
+        for ws in (False, True):
+            say(f"[{cfg}] {L.name} ws={ws} plan={hgc.conv2d_plan(L, ws).as_dict()}")
+            y = run_layer(L, x, w, b, use_ws=ws)
+            if ws:
+                pre, mag = cached
+            else:
+                pre, mag = oracle.conv2d_forward(L.desc(), x, w, b)
+                cached = (pre, mag)
+            ok, ratio, where = oracle.check(y, pre, mag, L.relu)
+            assert ok, f"{L} ws={ws}: |err|/bound={ratio:.3g} at {where}"
+            worst = max(worst, ratio)
+    say(f"[{cfg}] worst |err|/bound = {worst:.3f}")
+    assert worst <= 1.0
+
+
+@pytest.mark.parametrize("cfg,N", [("vgg16", 16), ("resnet50", 32), ("mobilenet_v1", 64)])
+def test_configs_full_batch_sampled(oracle, cfg, N):
+    """Full-size tensors in the launch configuration the benchmark uses; outputs the
+    oracle evaluates one by one: corners, edges, first and last image, random points."""
+    rng = np.random.default_rng(1234)
+    for i, L in enumerate(CONFIGS[cfg](N)):
+        x, w, b = make_tensors(L, seed=layer_seed(cfg, i))
+        say(f"[{cfg} N={N}] {L.name} plan={hgc.conv2d_plan(L, True).as_dict()}")
+        y = run_layer(L, x, w, b, use_ws=True)
+        idx = sample_points(L, rng, 4000)
+        assert_points(oracle, L, x, w, b, y, idx)
+        assert np.isfinite(y.astype(np.float32)).all()
