@@ -1,0 +1,175 @@
+#!/usr/bin/env python3
+"""Benchmark: FP16 conv-forward throughput on the VGG-16-shaped stack at N=1.
+
+A step is one pass of the whole hot path: the thirteen 3x3 convolution layers
+(bias + ReLU fused), each launched through the C ABI on its own seeded synthetic
+input already resident in HBM.  Prints ONE JSON line (see the keys below).
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--batch N] [--no-cpu]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_MFMA_F16 = 2516.6e12     # MI355X dense FP16 MFMA FLOP/s
+PEAK_HBM = 8.0e12             # MI355X HBM3E B/s
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--batch", type=int, default=1, help="images per layer call (headline: 1)")
+    ap.add_argument("--config", default="vgg16", help="workload table (headline: vgg16)")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    ap.add_argument("--no-ws", action="store_true", help="use the workspace-free entry point")
+    ap.add_argument("--per-layer", action="store_true", help="print a per-layer table to stderr")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU; --gpus must be 1 (no multi-GPU path exists)",
+              file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+    import paper_1901_00858_amd as hgc
+    from workloads import CONFIGS, layer_seed, make_tensors
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 3
+    hgc.load()
+    dev = torch.device("cuda:0")
+    layers = CONFIGS[args.config](args.batch)
+
+    # ---- inputs resident in HBM before any timing ----
+    host, bufs = [], []
+    for i, L in enumerate(layers):
+        x, w, b = make_tensors(L, seed=layer_seed(args.config, i))
+        host.append((x, w, b))
+        xd, wd, bd = (torch.from_numpy(a).to(dev) for a in (x, w, b))
+        y = torch.empty(L.y_shape, dtype=torch.float16, device=dev)
+        need = 0 if args.no_ws else hgc.conv2d_workspace_size(L)
+        ws = torch.empty(max(need, 1), dtype=torch.uint8, device=dev)
+        bufs.append((hgc.ConvDesc.make(L), xd, wd, bd, y, ws, need))
+    stream = torch.cuda.current_stream(dev)
+    sh = stream.cuda_stream
+
+    def launch(i):
+        d, xd, wd, bd, y, ws, need = bufs[i]
+        if args.no_ws:
+            st = hgc.forward_raw(d, xd.data_ptr(), wd.data_ptr(), bd.data_ptr(), y.data_ptr(), sh)
+        else:
+            st = hgc.forward_ws_raw(d, xd.data_ptr(), wd.data_ptr(), bd.data_ptr(), y.data_ptr(),
+                                    ws.data_ptr(), need, sh)
+        if st != 0:
+            raise hgc.HgcError(st, layers[i].name)
+
+    def step():
+        for i in range(len(layers)):
+            launch(i)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    flops_step = sum(L.flops for L in layers)
+    bytes_step = sum(L.bytes for L in layers)
+    tflops = flops_step / (ms_per_step * 1e-3) / 1e12
+
+    # ---- per-layer device time: HIP events on the launch stream around R launches ----
+    reps = max(5, min(50, args.steps))
+    per_layer = []
+    for i, L in enumerate(layers):
+        launch(i)
+        e0 = torch.cuda.Event(enable_timing=True)
+        e1 = torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        for _ in range(reps):
+            launch(i)
+        e1.record(stream)
+        e1.synchronize()
+        us = e0.elapsed_time(e1) * 1e3 / reps
+        plan = hgc.conv2d_plan(L, not args.no_ws).as_dict()
+        per_layer.append({
+            "layer": L.name, "path": plan["path_name"], "variant": plan["variant"],
+            "tile": [plan["tile_m"], plan["tile_h"], plan["tile_w"]], "split_k": plan["split_k"],
+            "grid": plan["grid"], "us": us, "tflops": L.flops / us / 1e6, "gbs": L.bytes / us / 1e3,
+            "flops": L.flops, "bytes": L.bytes,
+        })
+    # the dominant kernel: the layer class (same instantiation) with the largest summed time
+    groups = {}
+    for r in per_layer:
+        g = groups.setdefault((r["path"], r["variant"]), {"us": 0.0, "flops": 0, "bytes": 0, "n": 0, "layers": []})
+        g["us"] += r["us"]; g["flops"] += r["flops"]; g["bytes"] += r["bytes"]; g["n"] += 1
+        g["layers"].append(r["layer"])
+    key, dom = max(groups.items(), key=lambda kv: kv[1]["us"])
+    mfma_bound = (dom["flops"] / PEAK_MFMA_F16) >= (dom["bytes"] / PEAK_HBM)
+    if mfma_bound:
+        achieved = dom["flops"] / dom["us"] / 1e6          # TFLOP/s
+        roof = {"bound": "mfma", "achieved": achieved, "peak": PEAK_MFMA_F16 / 1e12, "unit": "TFLOP/s",
+                "frac": achieved / (PEAK_MFMA_F16 / 1e12), "traffic": None}
+    else:
+        achieved = dom["bytes"] / dom["us"] / 1e3          # GB/s
+        roof = {"bound": "hbm", "achieved": achieved, "peak": PEAK_HBM / 1e9, "unit": "GB/s",
+                "frac": achieved / (PEAK_HBM / 1e9), "traffic": None}
+    roof.update({"kernel": f"{key[0]}:variant{key[1]}", "layers": dom["layers"],
+                 "avg_launch_us": dom["us"] / dom["n"],
+                 "sum_layer_us": sum(r["us"] for r in per_layer)})
+
+    if args.per_layer:
+        for r in per_layer:
+            print("%-12s %-13s v%-2d tile %-14s split %-2d grid %-5d %9.2f us %8.1f TFLOP/s %8.1f GB/s" % (
+                r["layer"], r["path"], r["variant"], r["tile"], r["split_k"], r["grid"], r["us"],
+                r["tflops"], r["gbs"]), file=sys.stderr)
+
+    # ---- the oracle, as it stands, timed on the host cores (a reported baseline) ----
+    cpu = None
+    if not args.no_cpu:
+        import oracle
+        oracle.build()
+        sample = [i for i, L in enumerate(layers)] if args.batch == 1 else [len(layers) - 1]
+        t = time.perf_counter()
+        fl = 0
+        for i in sample:
+            x, w, b = host[i]
+            oracle.conv2d_forward(layers[i].desc(), x, w, b)
+            fl += layers[i].flops
+        dt = time.perf_counter() - t
+        cpu = {"value": fl / dt / 1e12, "unit": "TFLOP/s", "cores": oracle.num_threads(), "kind": "oracle",
+               "sample": "one pass over %d of the %d layers at N=%d (%.2f GFLOP, %.1f s)" % (
+                   len(sample), len(layers), args.batch, fl / 1e9, dt),
+               "ms_per_image": dt * 1e3 / args.batch if len(sample) == len(layers) else None}
+
+    out = {
+        "metric": "FP16 conv-forward TFLOP/s, VGG-16-shaped 13-layer stack",
+        "value": tflops, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "ms_per_image": ms_per_step / args.batch,
+        "pct_mfma_peak": 100.0 * tflops / (PEAK_MFMA_F16 / 1e12),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f16 (fp32 accumulate)", "data": "synthetic",
+        "config": {"workload": "%s conv stack, N=%d, 3x3 s1 p1, bias+ReLU, %d layers, %.2f GFLOP, %.1f MB" % (
+            args.config, args.batch, len(layers), flops_step / 1e9, bytes_step / 1e6),
+            "entry": "hgc_conv2d_forward" if args.no_ws else "hgc_conv2d_forward_ws"},
+        "roofline": roof,
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

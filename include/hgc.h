@@ -131,6 +131,12 @@ int32_t hgc_set_forced_path(int32_t path, int32_t tile_variant);
 /* Static, NUL-terminated description of a status code. */
 const char *hgc_status_string(hgc_status status);
 
+/*
+ * Runtime's description of the error behind the calling thread's most recent
+ * HGC_ERR_LAUNCH ("no error" text if the last launch succeeded). Static string.
+ */
+const char *hgc_last_launch_error(void);
+
 /* Library version: major * 10000 + minor * 100 + patch. */
 int32_t hgc_version(void);
 

@@ -21,7 +21,10 @@ PATH_NAMES = {1: "direct", 2: "igemm", 3: "igemm_splitk", 4: "depthwise"}
 class HgcError(RuntimeError):
     def __init__(self, status: int, where: str):
         self.status = status
-        super().__init__(f"{where}: {status_string(status)} (status {status})")
+        detail = ""
+        if status == -5:
+            detail = " [" + load().hgc_last_launch_error().decode() + "]"
+        super().__init__(f"{where}: {status_string(status)} (status {status}){detail}")
 
 
 class ConvDesc(ctypes.Structure):
@@ -86,6 +89,7 @@ def load():
     lib.hgc_status_string.argtypes = [ctypes.c_int32]
     lib.hgc_status_string.restype = ctypes.c_char_p
     lib.hgc_version.restype = ctypes.c_int32
+    lib.hgc_last_launch_error.restype = ctypes.c_char_p
     _lib = lib
     return lib
 

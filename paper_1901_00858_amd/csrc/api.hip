@@ -14,6 +14,7 @@ namespace hgc {
 
 static std::atomic<int> g_forced_path{HGC_PATH_AUTO};
 static std::atomic<int> g_forced_variant{-1};
+static thread_local int g_last_hip_error = 0;
 
 static constexpr long long kMaxLds = 160 * 1024;
 
@@ -210,21 +211,22 @@ static hgc_status run(const hgc_conv2d_desc *desc, const void *x, const void *w,
     a.y = static_cast<uint16_t *>(y);
     a.ws = static_cast<float *>(ws);
     hipStream_t s = static_cast<hipStream_t>(stream);
-    (void)hipGetLastError();
+    hipError_t e;
     switch (pl.pub.path) {
     case HGC_PATH_DEPTHWISE:
-        launch_depthwise(a, s);
+        e = launch_depthwise(a, s);
         break;
     case HGC_PATH_IGEMM:
     case HGC_PATH_IGEMM_SPLITK:
-        pl.variant->launch(a, dim3((unsigned)pl.pub.grid), s);
-        if (a.split_k > 1) launch_splitk_reduce(a, s);
+        e = pl.variant->launch(a, dim3((unsigned)pl.pub.grid), s);
+        if (e == hipSuccess && a.split_k > 1) e = launch_splitk_reduce(a, s);
         break;
     default:
-        launch_direct(a, s);
+        e = launch_direct(a, s);
         break;
     }
-    return hipGetLastError() == hipSuccess ? HGC_OK : HGC_ERR_LAUNCH;
+    g_last_hip_error = (int)e;
+    return e == hipSuccess ? HGC_OK : HGC_ERR_LAUNCH;
 }
 
 }  // namespace hgc
@@ -300,5 +302,10 @@ const char *hgc_status_string(hgc_status status)
 }
 
 int32_t hgc_version(void) { return 100; }
+
+const char *hgc_last_launch_error(void)
+{
+    return hipGetErrorString((hipError_t)g_last_hip_error);
+}
 
 }  // extern "C"

@@ -48,12 +48,13 @@ __global__ __launch_bounds__(256) void direct_kernel(const ConvArgs p)
     }
 }
 
-void launch_direct(const ConvArgs &a, hipStream_t stream)
+hipError_t launch_direct(const ConvArgs &a, hipStream_t stream)
 {
     const long long total = (long long)a.N * a.M * a.Ho * a.Wo;
     long long blocks = (total + 255) / 256;
     if (blocks > 1048576) blocks = 1048576;
     hipLaunchKernelGGL(direct_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, a);
+    return hipGetLastError();
 }
 
 // Depthwise (group == C == num_output): each output reads k*k inputs of its own
@@ -98,7 +99,7 @@ __global__ __launch_bounds__(256) void depthwise_kernel(const ConvArgs p)
     }
 }
 
-void launch_depthwise(const ConvArgs &a, hipStream_t stream)
+hipError_t launch_depthwise(const ConvArgs &a, hipStream_t stream)
 {
     const int chunks = (a.Ho * a.Wo + 255) / 256;
     long long blocks = (long long)a.N * a.C * chunks;
@@ -108,7 +109,8 @@ void launch_depthwise(const ConvArgs &a, hipStream_t stream)
     else if (a.ks == 5)
         hipLaunchKernelGGL(depthwise_kernel<5>, dim3((unsigned)blocks), dim3(256), 0, stream, a);
     else
-        launch_direct(a, stream);
+        return launch_direct(a, stream);
+    return hipGetLastError();
 }
 
 // Sum the FP32 slices of a split reduction in slice order (deterministic), then
@@ -128,12 +130,13 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const ConvArgs p)
     }
 }
 
-void launch_splitk_reduce(const ConvArgs &a, hipStream_t stream)
+hipError_t launch_splitk_reduce(const ConvArgs &a, hipStream_t stream)
 {
     const long long total = (long long)a.N * a.M * a.Ho * a.Wo;
     long long blocks = (total + 255) / 256;
     if (blocks > 65536) blocks = 65536;
     hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, a);
+    return hipGetLastError();
 }
 
 }  // namespace hgc

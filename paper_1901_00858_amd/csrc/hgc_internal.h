@@ -49,15 +49,15 @@ struct IgemmVariant {
     int calign;          // 1: Cg % 8 == 0, weights fetched as 16-byte vectors
     int max_rounds;      // capacity of the patch staging: max_rounds*256 items
     int lds_bytes;
-    void (*launch)(const ConvArgs &, dim3 grid, hipStream_t stream);
+    hipError_t (*launch)(const ConvArgs &, dim3 grid, hipStream_t stream);
     int BM() const { return 32 * wm_blocks * waves_m; }
     int BN() const { return 32 * wn_blocks * (4 / waves_m); }
 };
 
 const IgemmVariant *igemm_variants(int *count);
 
-void launch_direct(const ConvArgs &a, hipStream_t stream);
-void launch_depthwise(const ConvArgs &a, hipStream_t stream);
-void launch_splitk_reduce(const ConvArgs &a, hipStream_t stream);
+hipError_t launch_direct(const ConvArgs &a, hipStream_t stream);
+hipError_t launch_depthwise(const ConvArgs &a, hipStream_t stream);
+hipError_t launch_splitk_reduce(const ConvArgs &a, hipStream_t stream);
 
 }  // namespace hgc

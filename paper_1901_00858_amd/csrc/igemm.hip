@@ -17,6 +17,8 @@
 // Accumulation is FP32 in the MFMA accumulators (paper Section 3.1: overflow and
 // underflow arise during accumulation); bias, ReLU and the single FP32->FP16
 // rounding happen in registers before the store (no conversion pass, Section 3.3).
+#include <atomic>
+
 #include "hgc_internal.h"
 
 namespace hgc {
@@ -371,24 +373,36 @@ __global__ __launch_bounds__(256) void igemm_kernel(const ConvArgs p)
     }
 }
 
+// LDS beyond 64 KB per workgroup has to be requested per kernel; remember the
+// largest request so the attribute is set at most a few times per process.
+template <typename Kern>
+static hipError_t ensure_lds(Kern kern, size_t lds, std::atomic<size_t> &granted)
+{
+    if (lds <= 64 * 1024 || lds <= granted.load(std::memory_order_acquire)) return hipSuccess;
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e == hipSuccess) granted.store(lds, std::memory_order_release);
+    return e;
+}
+
 template <int KS, int A, int B, int WAVES_M, int NPL, int XVEC, bool CALIGN, int MAXR>
-static void launch_igemm(const ConvArgs &a, dim3 grid, hipStream_t stream)
+static hipError_t launch_igemm(const ConvArgs &a, dim3 grid, hipStream_t stream)
 {
     constexpr int W_UNITS = KS * KS * NPL * 32 * A * WAVES_M;
     const size_t lds = (size_t)(W_UNITS + NPL * a.PH * a.PWU) * 16;
+    hipError_t e;
     if (a.split_k > 1) {
+        static std::atomic<size_t> granted{0};
         auto kern = igemm_kernel<KS, A, B, WAVES_M, NPL, XVEC, CALIGN, MAXR, true>;
-        static bool once = (hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                                hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024), true);
-        (void)once;
+        if ((e = ensure_lds(kern, lds, granted)) != hipSuccess) return e;
         hipLaunchKernelGGL(kern, grid, dim3(256), lds, stream, a);
     } else {
+        static std::atomic<size_t> granted{0};
         auto kern = igemm_kernel<KS, A, B, WAVES_M, NPL, XVEC, CALIGN, MAXR, false>;
-        static bool once = (hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                                hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024), true);
-        (void)once;
+        if ((e = ensure_lds(kern, lds, granted)) != hipSuccess) return e;
         hipLaunchKernelGGL(kern, grid, dim3(256), lds, stream, a);
     }
+    return hipGetLastError();
 }
 
 #define HGC_VARIANT(KS, A, B, WM, NPL, XVEC, CAL, MAXR)                                        \
