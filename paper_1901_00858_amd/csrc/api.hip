@@ -6,6 +6,7 @@
 #include <algorithm>
 #include <atomic>
 #include <climits>
+#include <cmath>
 #include <cstring>
 
 #include "hgc_internal.h"
@@ -65,32 +66,44 @@ static void base_args(const Geometry &g, ConvArgs *a)
 
 static int ceil_div(long long a, long long b) { return (int)((a + b - 1) / b); }
 
-// Pick the output-window shape (tile_w = 2^j columns, tile_h = BN / tile_w rows)
-// that wastes the fewest accumulator columns on pixels outside the image, and fits LDS.
-static bool choose_window(const Geometry &g, const IgemmVariant &v, ConvArgs *a, long long *lds_out)
+// ---- choice of tile shape, output window and reduction split -----------------
+// A candidate is (kernel instantiation, window tile_h x tile_w, split).  Its cost
+// is a coarse cycle estimate: workgroups run in rounds over the 256 CUs; one
+// workgroup costs a fixed ramp plus, per channel block, the larger of its MFMA
+// time and its staging time, plus the epilogue.  The constants were fitted to
+// rocprofv3 kernel durations on MI355X; only the ranking matters.
+struct Candidate {
+    const IgemmVariant *v;
+    int log2_tw, tiles_w, tiles_h, tiles_m, PH, PWU, nsteps, split, steps_per_split;
+    long long lds, grid;
+    double cycles;
+};
+
+static double estimate_cycles(const Geometry &g, const Candidate &c)
 {
-    const int BN = v.BN();
-    double best = 1e30;
-    bool found = false;
-    for (int j = 2; (1 << j) <= BN && j <= 6; ++j) {
-        const int TW = 1 << j, TH = BN >> j;
-        const int tiles_w = ceil_div(g.Wo, TW), tiles_h = ceil_div(g.Ho, TH);
-        const int PH = (TH - 1) * g.s + g.k;
-        const int PW = (TW - 1) * g.s + g.k;
-        const int PWU = (v.xvec == 2) ? 2 * ((PW + 2) / 2) : PW;
-        const long long lds = (long long)v.lds_bytes + 16LL * v.npl * PH * PWU;
-        if (lds > kMaxLds) continue;
-        // cost: padded pixel slots, with a mild preference for wide rows (coalesced stores)
-        double cost = (double)tiles_w * TW * tiles_h * TH / ((double)g.Wo * g.Ho);
-        cost *= 1.0 + 0.02 * (6 - j);
-        if (cost < best) {
-            best = cost; found = true;
-            a->log2_tw = j; a->tiles_w = tiles_w; a->tiles_h = tiles_h;
-            a->PH = PH; a->PWU = PWU;
-            *lds_out = lds;
-        }
+    const IgemmVariant &v = *c.v;
+    const int T = v.ks * v.ks;
+    const double waves_per_simd = v.threads() / 256.0 > 1.0 ? v.threads() / 256.0 : 1.0;
+    const double mfma = 32.0 * v.wm_blocks * v.wn_blocks * T * (v.npl / 2) * waves_per_simd;
+    const double stage_bytes = 16.0 * T * v.npl * v.BM() * 1.4 + 16.0 * v.npl * c.PH * c.PWU * 2.5;
+    const double scalar_penalty = (v.calign ? 1.0 : 4.0) * (v.xvec == 2 ? 1.0 : 1.5);
+    const double stage = stage_bytes / 40.0 * scalar_penalty;
+    const double step = (v.nstage == 2 ? std::max(mfma, stage) + 300.0 : mfma + stage + 600.0);
+    const double epilogue = 25.0 * 16 * v.wm_blocks * v.wn_blocks * waves_per_simd;
+    const double wg = 4000.0 + stage + c.steps_per_split * step + epilogue;
+    int wg_per_cu = (int)(kMaxLds / std::max<long long>(c.lds, 1));
+    const int by_threads = 1024 / v.threads() >= 1 ? 1024 / v.threads() : 1;   // 512 VGPR budget: <= 4 waves/SIMD
+    wg_per_cu = std::max(1, std::min(wg_per_cu, std::min(by_threads, 2)));
+    const double slots = 256.0 * wg_per_cu;
+    const double rounds = std::ceil((double)c.grid * c.split / slots);
+    // co-resident workgroups share the CU: their MFMA work serialises
+    const double share = (wg_per_cu > 1 && (double)c.grid * c.split > 256.0) ? 1.0 + 0.6 * (wg_per_cu - 1) : 1.0;
+    double total = rounds * wg * share;
+    if (c.split > 1) {
+        const double ws_bytes = 4.0 * c.split * g.N * (double)g.M * g.Ho * g.Wo;
+        total += 9000.0 + 2.0 * ws_bytes / 1500.0;     // write + read of the partial sums, second launch
     }
-    return found;
+    return total;
 }
 
 static bool plan_igemm(const Geometry &g, bool with_ws, bool x_al4, bool w_al16, int forced_variant,
@@ -100,55 +113,62 @@ static bool plan_igemm(const Geometry &g, bool with_ws, bool x_al4, bool w_al16,
     const IgemmVariant *vs = igemm_variants(&nv);
     const int want_xvec = (g.W % 2 == 0 && x_al4) ? 2 : 1;
     const int want_cal = (g.Cg % 8 == 0 && w_al16) ? 1 : 0;
-    const IgemmVariant *pick = nullptr;
-    if (forced_variant >= 0) {
-        if (forced_variant >= nv) return false;
-        const IgemmVariant &v = vs[forced_variant];
-        if (v.ks != g.k) return false;
-        if (v.xvec == 2 && want_xvec != 2) return false;
-        if (v.calign && !want_cal) return false;
-        pick = &v;
-    } else {
-        for (int i = 0; i < nv; ++i) {
-            const IgemmVariant &v = vs[i];
-            if (v.ks != g.k || v.xvec != want_xvec || v.calign != want_cal) continue;
-            if (!pick) { pick = &v; continue; }
-            // prefer the tile with less channel padding; ties go to the larger tile
-            const long long pad_new = (long long)ceil_div(g.Mg, v.BM()) * v.BM();
-            const long long pad_old = (long long)ceil_div(g.Mg, pick->BM()) * pick->BM();
-            if (pad_new < pad_old) pick = &v;
+    Candidate best;
+    best.v = nullptr;
+    best.cycles = 1e300;
+    for (int i = 0; i < nv; ++i) {
+        const IgemmVariant &v = vs[i];
+        if (v.ks != g.k) continue;
+        if (forced_variant >= 0) {
+            if (i != forced_variant) continue;
+            if ((v.xvec == 2 && want_xvec != 2) || (v.calign && !want_cal)) continue;
+        } else if (v.xvec != want_xvec || v.calign != want_cal) {
+            continue;
+        }
+        const int BN = v.BN();
+        for (int j = 2; (1 << j) <= BN && j <= 6; ++j) {
+            Candidate c;
+            c.v = &v;
+            c.log2_tw = j;
+            const int TW = 1 << j, TH = BN >> j;
+            c.tiles_w = ceil_div(g.Wo, TW);
+            c.tiles_h = ceil_div(g.Ho, TH);
+            c.tiles_m = ceil_div(g.Mg, v.BM());
+            c.PH = (TH - 1) * g.s + g.k;
+            const int PW = (TW - 1) * g.s + g.k;
+            c.PWU = (v.xvec == 2) ? 2 * ((PW + 2) / 2) : PW;
+            c.lds = std::max(v.nstage * (v.w_lds_bytes() + 16LL * v.npl * c.PH * c.PWU), v.epilogue_lds_bytes());
+            if (c.lds > kMaxLds) continue;
+            c.nsteps = ceil_div(g.Cg, 8 * v.npl);
+            c.grid = (long long)c.tiles_m * c.tiles_w * c.tiles_h * g.G * g.N;
+            if (c.grid > (1 << 30)) continue;
+            const int max_split = (with_ws && c.nsteps >= 2) ? std::min(c.nsteps, 32) : 1;
+            for (int sp = 1; sp <= max_split; sp = (sp < 4 ? sp + 1 : sp * 2)) {
+                if (force_split && sp < 2 && max_split >= 2) continue;
+                c.steps_per_split = ceil_div(c.nsteps, sp);
+                c.split = ceil_div(c.nsteps, c.steps_per_split);
+                if (c.grid * c.split > (1 << 30)) continue;
+                c.cycles = estimate_cycles(g, c);
+                if (c.cycles < best.cycles) best = c;
+            }
         }
     }
-    if (!pick) return false;
+    if (!best.v) return false;
     ConvArgs *a = &pl->args;
-    long long lds = 0;
-    if (!choose_window(g, *pick, a, &lds)) return false;
-    a->tiles_m = ceil_div(g.Mg, pick->BM());
-    a->nsteps = ceil_div(g.Cg, 8 * pick->npl);
-    long long grid = (long long)a->tiles_m * a->tiles_w * a->tiles_h * g.G * g.N;
-    int split = 1;
-    if (with_ws && a->nsteps >= 2) {
-        // too few workgroups for 256 CUs: slice the channel blocks
-        if (grid < 192 || force_split) {
-            split = (int)((384 + grid - 1) / grid);
-            if (split > a->nsteps) split = a->nsteps;
-            if (split > 32) split = 32;
-            if (force_split && split < 2) split = 2;
-        }
-    }
-    a->steps_per_split = ceil_div(a->nsteps, split);
-    a->split_k = ceil_div(a->nsteps, a->steps_per_split);
-    if (grid * a->split_k > INT_MAX) return false;
-    pl->variant = pick;
+    a->log2_tw = best.log2_tw; a->tiles_w = best.tiles_w; a->tiles_h = best.tiles_h;
+    a->tiles_m = best.tiles_m; a->PH = best.PH; a->PWU = best.PWU;
+    a->nsteps = best.nsteps; a->split_k = best.split; a->steps_per_split = best.steps_per_split;
+    a->grid_blocks = (int)(best.grid * best.split);
+    pl->variant = best.v;
     pl->pub.path = a->split_k > 1 ? HGC_PATH_IGEMM_SPLITK : HGC_PATH_IGEMM;
-    pl->pub.tile_m = pick->BM();
+    pl->pub.tile_m = best.v->BM();
     pl->pub.tile_w = 1 << a->log2_tw;
-    pl->pub.tile_h = pick->BN() >> a->log2_tw;
+    pl->pub.tile_h = best.v->BN() >> a->log2_tw;
     pl->pub.split_k = a->split_k;
-    pl->pub.variant = (int)(pick - vs);
-    pl->pub.grid = (int)(grid * a->split_k);
-    pl->pub.block = 256;
-    pl->pub.lds_bytes = lds;
+    pl->pub.variant = (int)(best.v - vs);
+    pl->pub.grid = a->grid_blocks;
+    pl->pub.block = best.v->threads();
+    pl->pub.lds_bytes = best.lds;
     pl->pub.workspace_bytes =
         a->split_k > 1 ? 4LL * a->split_k * g.N * g.M * g.Ho * g.Wo : 0;
     return true;
@@ -210,6 +230,11 @@ static hgc_status run(const hgc_conv2d_desc *desc, const void *x, const void *w,
     a.b = static_cast<const uint16_t *>(b);
     a.y = static_cast<uint16_t *>(y);
     a.ws = static_cast<float *>(ws);
+    {   // widest output store: divides Wo and the window width, and y's byte alignment allows it
+        int ov = 8;
+        while (ov > 1 && (g.Wo % ov || (1 << a.log2_tw) % ov || ((uintptr_t)y % (2 * ov)))) ov >>= 1;
+        a.out_vec = ov;
+    }
     hipStream_t s = static_cast<hipStream_t>(stream);
     hipError_t e;
     switch (pl.pub.path) {
@@ -218,7 +243,7 @@ static hgc_status run(const hgc_conv2d_desc *desc, const void *x, const void *w,
         break;
     case HGC_PATH_IGEMM:
     case HGC_PATH_IGEMM_SPLITK:
-        e = pl.variant->launch(a, dim3((unsigned)pl.pub.grid), s);
+        e = pl.variant->launch(a, s);
         if (e == hipSuccess && a.split_k > 1) e = launch_splitk_reduce(a, s);
         break;
     default:

@@ -34,6 +34,8 @@ struct ConvArgs {
     int tiles_w, tiles_h, tiles_m;
     int PH, PWU;         // input halo patch: rows, and 16-byte units (pixels) per row
     int nsteps;          // channel blocks of CB channels per group: ceil(Cg / CB)
+    int out_vec;         // output pixels per store (8, 4, 2 or 1): divides Wo and tile_w, fits y's alignment
+    int grid_blocks;     // workgroups that have work (the launch pads to a multiple of 8)
     int split_k;         // reduction slices (1 = none)
     int steps_per_split; // channel blocks per slice
 };
@@ -43,15 +45,19 @@ struct IgemmVariant {
     int ks;              // compile-time kernel extent (1, 3, 5, 7)
     int wm_blocks;       // 32-row blocks of output channels per wave
     int wn_blocks;       // 32-pixel blocks per wave
-    int waves_m;         // waves along M (waves along N = 4 / waves_m)
+    int waves_m;         // waves along output channels
+    int waves_n;         // waves along pixels
     int npl;             // 8-channel planes per K step (CB = 8 * npl)
     int xvec;            // pixels per global load of the input (1 or 2)
     int calign;          // 1: Cg % 8 == 0, weights fetched as 16-byte vectors
-    int max_rounds;      // capacity of the patch staging: max_rounds*256 items
-    int lds_bytes;
-    hipError_t (*launch)(const ConvArgs &, dim3 grid, hipStream_t stream);
+    int nstage;          // LDS buffers (2 = double buffered)
+    int max_rounds;      // patch staging rounds pipelined through registers
+    hipError_t (*launch)(const ConvArgs &, hipStream_t stream);
     int BM() const { return 32 * wm_blocks * waves_m; }
-    int BN() const { return 32 * wn_blocks * (4 / waves_m); }
+    int BN() const { return 32 * wn_blocks * waves_n; }
+    int threads() const { return 64 * waves_m * waves_n; }
+    long long w_lds_bytes() const { return 16LL * ks * ks * npl * BM(); }
+    long long epilogue_lds_bytes() const { return 80LL * 32 * wm_blocks * waves_m * waves_n; }
 };
 
 const IgemmVariant *igemm_variants(int *count);

@@ -17,6 +17,17 @@
 // Accumulation is FP32 in the MFMA accumulators (paper Section 3.1: overflow and
 // underflow arise during accumulation); bias, ReLU and the single FP32->FP16
 // rounding happen in registers before the store (no conversion pass, Section 3.3).
+//
+// Staging.  Input: each item is XVEC pixels x 8 channels; eight coalesced loads
+// (one per channel plane of NCHW) are transposed in registers with v_perm_b32
+// into XVEC 16-byte units.  Weights: each wave owns BM/NW rows; it fetches their
+// contiguous CB*k*k-half runs with coalesced 16-byte LDS-direct loads
+// (global_load_lds_dwordx4) into its own slice of the LDS weight buffer, reads
+// them back one (row, plane) per lane and writes the regrouped units over the
+// same slice (LDS operations of one wave execute in order, so no barrier is
+// needed inside the wave).
+// With NSTAGE = 2 the LDS buffers are double: the loads of step s+1 are issued
+// before the MFMAs of step s and land in the other buffer half-way through them.
 #include <atomic>
 
 #include "hgc_internal.h"
@@ -110,28 +121,35 @@ __device__ __forceinline__ void store_patch_item(u32x4 *xl, const PatchItem &it,
 }
 
 // KS: kernel extent.  A, B: 32x32 accumulator blocks per wave along channels and
-// pixels.  WAVES_M: waves along channels (4 waves per workgroup).  NPL: 8-channel
-// planes per K step.  XVEC: input pixels per global load (2 needs even W and a
-// 4-byte aligned base).  CALIGN: Cg % 8 == 0 and a 16-byte aligned weight base.
-// MAXR: staging rounds of the patch that are prefetched through registers.
-// SPLITK: write FP32 partial sums of a slice of the channel blocks.
-template <int KS, int A, int B, int WAVES_M, int NPL, int XVEC, bool CALIGN, int MAXR, bool SPLITK>
-__global__ __launch_bounds__(256) void igemm_kernel(const ConvArgs p)
+// pixels.  WAVES_M x WAVES_N waves per workgroup.  NPL: 8-channel planes per K
+// step.  XVEC: input pixels per global load (2 needs even W and a 4-byte aligned
+// base).  CALIGN: Cg % 8 == 0 and a 16-byte aligned weight base.  NSTAGE: LDS
+// buffers (1 or 2).  MAXR: patch staging rounds held in registers.  SPLITK: write
+// FP32 partial sums of a slice of the channel blocks instead of the output.
+template <int KS, int A, int B, int WAVES_M, int WAVES_N, int NPL, int XVEC, bool CALIGN, int NSTAGE,
+          int MAXR, bool SPLITK>
+__global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void igemm_kernel(const ConvArgs p)
 {
-    constexpr int WAVES_N = 4 / WAVES_M;
+    constexpr int NW = WAVES_M * WAVES_N;
+    constexpr int NT = 64 * NW;
     constexpr int BM = 32 * A * WAVES_M;
     constexpr int BN = 32 * B * WAVES_N;
     constexpr int T = KS * KS;
     constexpr int CB = 8 * NPL;
     constexpr int W_UNITS = T * NPL * BM;
-    constexpr int W_ITEMS = BM * NPL;
-    constexpr int WR = (W_ITEMS + 255) / 256;
-    constexpr bool WPREFETCH = CALIGN && (T * WR <= 9);
+    constexpr int RPW = BM / NW;                 // weight rows staged by one wave
+    constexpr int CPR = NPL * T;                 // 16-byte chunks per row per step
+    constexpr int WCH = RPW * CPR;               // chunks (= LDS units) per wave
+    constexpr int WLR = (WCH + 63) / 64;         // load rounds per lane
+    constexpr int WIT = RPW * NPL;               // (row, plane) items per wave
+    constexpr int WIR = (WIT + 63) / 64;
+    constexpr bool WPREFETCH = CALIGN;
     static_assert(NPL % 2 == 0, "planes come in pairs (16 channels per MFMA)");
+    static_assert(BM % NW == 0 && (RPW & (RPW - 1)) == 0, "rows per wave must be a power of two");
 
     extern __shared__ u32x4 lds[];
-    u32x4 *wl = lds;              // [T][NPL][BM]
-    u32x4 *xl = lds + W_UNITS;    // [NPL][PH][PWU]
+    const int X_UNITS = NPL * p.PH * p.PWU;
+    const int stage_units = W_UNITS + X_UNITS;   // [stage]{ W[wave][T][NPL][RPW] , X[NPL][PH][PWU] }
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -141,7 +159,15 @@ __global__ __launch_bounds__(256) void igemm_kernel(const ConvArgs p)
     const int l32 = lane & 31;
     const int lh = lane >> 5;
 
-    int bid = blockIdx.x;
+    // Workgroup ids are dealt round-robin to the 8 XCDs; renumber so that each XCD
+    // (one L2) works on a contiguous range of tiles, which share patches and weights.
+    const int nblk = p.grid_blocks;
+    int bid;
+    {
+        const int per = (nblk + 7) >> 3;
+        bid = (blockIdx.x & 7) * per + (blockIdx.x >> 3);
+        if (bid >= nblk) return;                 // padding workgroups of the last XCD rows
+    }
     const int tm = bid % p.tiles_m; bid /= p.tiles_m;
     const int twi = bid % p.tiles_w; bid /= p.tiles_w;
     const int thi = bid % p.tiles_h; bid /= p.tiles_h;
@@ -163,19 +189,18 @@ __global__ __launch_bounds__(256) void igemm_kernel(const ConvArgs p)
     const int Cg = p.Cg, Mg = p.Mg;
 
     // ---- staging maps (do not depend on the K step) ----
-    const int ipr = PWU / XVEC;                 // items per patch row
+    const int ipr = PWU / XVEC;                  // items per patch row
     const int total_items = NPL * PH * ipr;
-    const int rounds = (total_items + 255) >> 8;
+    const int rounds = (total_items + NT - 1) / NT;
     PatchItem pit[MAXR];
 #pragma unroll
     for (int r = 0; r < MAXR; ++r)
-        pit[r] = decode_patch_item<XVEC>(r * 256 + tid, total_items, ipr, PH, PWU, ih0, iwa, p.H, p.W, HW);
+        pit[r] = decode_patch_item<XVEC>(r * NT + tid, total_items, ipr, PH, PWU, ih0, iwa, p.H, p.W, HW);
 
     const uint16_t *xg = p.x + ((size_t)n * p.C + (size_t)g * Cg) * HW;
     const uint16_t *wg = p.w + (size_t)g * Mg * Cg * T;
 
     uint32_t xreg[MAXR][8];
-    u32x4 wreg[WPREFETCH ? WR : 1][T];
 
     auto load_x = [&](int st) {
         const uint16_t *xcb = xg + (size_t)st * CB * HW;
@@ -183,14 +208,14 @@ __global__ __launch_bounds__(256) void igemm_kernel(const ConvArgs p)
         for (int r = 0; r < MAXR; ++r)
             load_patch_item<XVEC, CALIGN>(xcb, pit[r], st * CB, Cg, HW, xreg[r]);
     };
-    auto store_x = [&](int st) {
+    auto store_x = [&](int st, u32x4 *xl) {
 #pragma unroll
         for (int r = 0; r < MAXR; ++r) store_patch_item<XVEC>(xl, pit[r], xreg[r]);
-        // patches larger than the prefetch capacity: remaining rounds, not pipelined
+        // patches larger than the register capacity: remaining rounds, not pipelined
         if (rounds > MAXR) {
             const uint16_t *xcb = xg + (size_t)st * CB * HW;
             for (int r = MAXR; r < rounds; ++r) {
-                PatchItem it = decode_patch_item<XVEC>(r * 256 + tid, total_items, ipr, PH, PWU,
+                PatchItem it = decode_patch_item<XVEC>(r * NT + tid, total_items, ipr, PH, PWU,
                                                        ih0, iwa, p.H, p.W, HW);
                 uint32_t d[8];
                 load_patch_item<XVEC, CALIGN>(xcb, it, st * CB, Cg, HW, d);
@@ -199,80 +224,99 @@ __global__ __launch_bounds__(256) void igemm_kernel(const ConvArgs p)
         }
     };
 
-    // weights: item = (row m of the tile, plane); T taps x 8 channels each
-    auto load_w_vec = [&](int st, int r, u32x4 (&wv)[T]) {
-        const int id = r * 256 + tid;
-        const int m = id % BM, pl = id / BM;
-        const bool ok = (id < W_ITEMS) && (m0 + m < Mg) && (st * CB + pl * 8 < Cg);
-        const u32x4 *src = reinterpret_cast<const u32x4 *>(
-            wg + ((size_t)(m0 + m) * Cg + st * CB + pl * 8) * T);
+    // ---- weights ----
+    // Raw rows go from global memory straight into this wave's slice of an LDS weight
+    // buffer (global_load_lds, 16 bytes per lane, consecutive lanes -> consecutive
+    // units); rows or planes outside the problem are fetched from a valid dummy
+    // address and zeroed when they are regrouped.
+    int wofs[WPREFETCH ? WLR : 1];
+    if (WPREFETCH) {
 #pragma unroll
-        for (int t = 0; t < T; ++t) {
-            u32x4 v = {0u, 0u, 0u, 0u};
-            if (ok) v = src[t];
-            wv[t] = v;
+        for (int k = 0; k < WLR; ++k) {
+            const int id = lane + 64 * k;
+            const int row = id / CPR, j = id % CPR;
+            const int m = m0 + wave * RPW + row;
+            // -1: row outside the problem; plane validity depends on the step
+            wofs[k] = (id < WCH && m < Mg) ? (m * Cg * T + j * 8) : -1;
+        }
+    }
+    auto load_w = [&](int st, u32x4 *wl) {
+        if (!WPREFETCH) return;
+        u32x4 *mine = wl + wave * WCH;
+#pragma unroll
+        for (int k = 0; k < WLR; ++k) {
+            const int id = lane + 64 * k;
+            const int j = id % CPR;
+            const bool ok = (wofs[k] >= 0) && (st * CB + (j / T) * 8 < Cg);
+            const uint16_t *src = ok ? (wg + (size_t)wofs[k] + (size_t)st * CB * T) : wg;
+            if (id < WCH)
+                __builtin_amdgcn_global_load_lds(
+                    (const __attribute__((address_space(1))) void *)src,
+                    (__attribute__((address_space(3))) void *)(mine + 64 * k), 16, 0, 0);
         }
     };
-    auto store_w_vec = [&](int r, const u32x4 (&wv)[T]) {
-        const int id = r * 256 + tid;
-        if (id >= W_ITEMS) return;
-        const int m = id % BM, pl = id / BM;
-        // wv as 4T dwords holds halves e = c*T + tap (c = 0..7); regroup per tap
+    auto store_w = [&](int st, u32x4 *wl) {
+        u32x4 *mine = wl + wave * WCH;           // this wave's slice: final layout [T][NPL][RPW]
+        if (WPREFETCH) {
+            // the raw rows ([row][CPR] chunks) have landed (caller waited on vmcnt);
+            // read back one (row, plane) per lane: halves e = c*T + tap, c = 0..7 ...
+            u32x4 rr[WIR][T];
 #pragma unroll
-        for (int t = 0; t < T; ++t) {
-            uint32_t o[4];
+            for (int k = 0; k < WIR; ++k) {
+                const int item = lane + 64 * k;
+                const int row = item % RPW, pl = item / RPW;
+                if (item < WIT) {
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int ea = (2 * i) * T + t, eb = (2 * i + 1) * T + t;
-                const int da = ea >> 1, db = eb >> 1;
-                const uint32_t va = wv[da >> 2][da & 3];
-                const uint32_t vb = wv[db >> 2][db & 3];
-                const uint32_t sel = ((ea & 1) ? 0x0302u : 0x0100u) | (((eb & 1) ? 0x0706u : 0x0504u) << 16);
-                o[i] = __builtin_amdgcn_perm(vb, va, sel);
-            }
-            u32x4 u = {o[0], o[1], o[2], o[3]};
-            wl[(t * NPL + pl) * BM + m] = u;
-        }
-    };
-    auto stage_w_scalar = [&](int st) {    // any Cg, any alignment: 2-byte loads
-        for (int r = 0; r < WR; ++r) {
-            const int id = r * 256 + tid;
-            if (id >= W_ITEMS) continue;
-            const int m = id % BM, pl = id / BM;
-            const bool rowok = (m0 + m < Mg);
-            const int c0 = st * CB + pl * 8;
-            const uint16_t *src = wg + ((size_t)(m0 + m) * Cg + c0) * T;
-            for (int t = 0; t < T; ++t) {
-                uint32_t h[8];
-#pragma unroll
-                for (int j = 0; j < 8; ++j) {
-                    uint32_t v = 0;
-                    if (rowok && (c0 + j < Cg)) v = src[j * T + t];
-                    h[j] = v;
+                    for (int t = 0; t < T; ++t) rr[k][t] = mine[row * CPR + pl * T + t];
                 }
-                u32x4 u = {h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16)};
-                wl[(t * NPL + pl) * BM + m] = u;
             }
-        }
-    };
-    auto load_w = [&](int st) {
-        if (WPREFETCH) {
+            // ... and write one unit per tap: the 8 channels of (row, tap)
 #pragma unroll
-            for (int r = 0; r < WR; ++r) load_w_vec(st, r, wreg[r]);
-        }
-    };
-    auto store_w = [&](int st) {
-        if (WPREFETCH) {
+            for (int k = 0; k < WIR; ++k) {
+                const int item = lane + 64 * k;
+                const int row = item % RPW, pl = item / RPW;
+                if (item < WIT) {
+                    const bool ok = (m0 + wave * RPW + row < Mg) && (st * CB + pl * 8 < Cg);
 #pragma unroll
-            for (int r = 0; r < WR; ++r) store_w_vec(r, wreg[r]);
-        } else if (CALIGN) {
-            for (int r = 0; r < WR; ++r) {
-                u32x4 wv[T];
-                load_w_vec(st, r, wv);
-                store_w_vec(r, wv);
+                    for (int t = 0; t < T; ++t) {
+                        uint32_t o[4];
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) {
+                            const int ea = (2 * i) * T + t, eb = (2 * i + 1) * T + t;
+                            const int da = ea >> 1, db = eb >> 1;
+                            const uint32_t va = rr[k][da >> 2][da & 3];
+                            const uint32_t vb = rr[k][db >> 2][db & 3];
+                            const uint32_t sel = ((ea & 1) ? 0x0302u : 0x0100u) |
+                                                 (((eb & 1) ? 0x0706u : 0x0504u) << 16);
+                            o[i] = ok ? __builtin_amdgcn_perm(vb, va, sel) : 0u;
+                        }
+                        u32x4 u = {o[0], o[1], o[2], o[3]};
+                        mine[(t * NPL + pl) * RPW + row] = u;
+                    }
+                }
             }
         } else {
-            stage_w_scalar(st);
+            // any Cg, any alignment: 2-byte loads straight into the final layout
+            for (int k = 0; k < WIR; ++k) {
+                const int item = lane + 64 * k;
+                if (item >= WIT) continue;
+                const int row = item % RPW, pl = item / RPW;
+                const int m = m0 + wave * RPW + row;
+                const int c0 = st * CB + pl * 8;
+                const uint16_t *src = wg + ((size_t)m * Cg + c0) * T;
+                for (int t = 0; t < T; ++t) {
+                    uint32_t h[8];
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) {
+                        uint32_t v = 0;
+                        if (m < Mg && (c0 + j < Cg)) v = src[j * T + t];
+                        h[j] = v;
+                    }
+                    u32x4 u = {h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16),
+                               h[6] | (h[7] << 16)};
+                    mine[(t * NPL + pl) * RPW + row] = u;
+                }
+            }
         }
     };
 
@@ -284,7 +328,12 @@ __global__ __launch_bounds__(256) void igemm_kernel(const ConvArgs p)
         const int th = pix >> p.log2_tw, tw = pix & (TW - 1);
         xb[j] = (lh * PH + th * s) * PWU + tw * s + cofs;
     }
-    const int ab = lh * BM + wm * (32 * A) + l32;
+    int ab[A];                                   // row -> (owning wave slice, row within it)
+#pragma unroll
+    for (int i = 0; i < A; ++i) {
+        const int m = wm * (32 * A) + i * 32 + l32;
+        ab[i] = (m / RPW) * WCH + lh * RPW + (m % RPW);
+    }
     const int plane_pair_stride = 2 * PH * PWU;
 
     floatx16 acc[A][B];
@@ -295,9 +344,10 @@ __global__ __launch_bounds__(256) void igemm_kernel(const ConvArgs p)
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
 
-    auto compute = [&]() {
+    auto compute = [&](const u32x4 *wl, const u32x4 *xl, int t0, int t1) {
 #pragma unroll
         for (int t = 0; t < T; ++t) {
+            if (t < t0 || t >= t1) continue;
             const int r = t / KS, q = t % KS;
             const int toff = r * PWU + q;
 #pragma unroll
@@ -305,7 +355,7 @@ __global__ __launch_bounds__(256) void igemm_kernel(const ConvArgs p)
                 half8 af[A], bf[B];
 #pragma unroll
                 for (int i = 0; i < A; ++i)
-                    af[i] = __builtin_bit_cast(half8, wl[(t * NPL + pp * 2) * BM + ab + i * 32]);
+                    af[i] = __builtin_bit_cast(half8, wl[ab[i] + (t * NPL + pp * 2) * RPW]);
 #pragma unroll
                 for (int j = 0; j < B; ++j)
                     bf[j] = __builtin_bit_cast(half8, xl[xb[j] + toff + pp * plane_pair_stride]);
@@ -324,49 +374,133 @@ __global__ __launch_bounds__(256) void igemm_kernel(const ConvArgs p)
         st0 = ksl * p.steps_per_split;
         st1 = min(p.nsteps, st0 + p.steps_per_split);
     }
-    if (st0 < st1) {
-        load_x(st0);
-        load_w(st0);
-    }
-    for (int st = st0; st < st1; ++st) {
-        __syncthreads();
-        store_x(st);
-        store_w(st);
-        __syncthreads();
-        if (st + 1 < st1) {
-            load_x(st + 1);
-            load_w(st + 1);
+    // all outstanding vector-memory operations (patch loads and LDS-direct weight rows)
+    auto wait_vmem = [&]() { __builtin_amdgcn_s_waitcnt(0x0F70); };
+    if (NSTAGE == 2) {
+        if (st0 < st1) {
+            load_x(st0);
+            load_w(st0, lds);
+            wait_vmem();
+            store_x(st0, lds + W_UNITS);
+            store_w(st0, lds);
         }
-        compute();
+        __syncthreads();
+        for (int st = st0; st < st1; ++st) {
+            const int cur = (st - st0) & 1;
+            u32x4 *wl = lds + cur * stage_units, *xl = wl + W_UNITS;
+            u32x4 *wn_ = lds + (cur ^ 1) * stage_units, *xn_ = wn_ + W_UNITS;
+            const bool more = st + 1 < st1;
+            if (more) {
+                load_x(st + 1);
+                load_w(st + 1, wn_);
+            }
+            // the loads get the whole step's MFMA time to arrive
+            compute(wl, xl, 0, T);
+            if (more) {
+                wait_vmem();
+                store_x(st + 1, xn_);
+                store_w(st + 1, wn_);
+            }
+            __syncthreads();
+        }
+    } else {
+        u32x4 *wl = lds, *xl = lds + W_UNITS;
+        if (st0 < st1) load_x(st0);
+        for (int st = st0; st < st1; ++st) {
+            __syncthreads();                      // everyone is done reading the buffers
+            load_w(st, wl);
+            wait_vmem();
+            store_x(st, xl);
+            store_w(st, wl);
+            __syncthreads();
+            if (st + 1 < st1) load_x(st + 1);
+            compute(wl, xl, 0, T);
+        }
     }
 
     // ---- epilogue: accumulator register e of lane (l32, lh) in block (i, j) is
     // channel row 8*(e/4) + 4*lh + e%4 and pixel column l32 of that block ----
     const int HoWo = p.Ho * p.Wo;
+    if (SPLITK) {
+        // FP32 partial sums of this slice: 32 consecutive pixels per row and instruction
+#pragma unroll
+        for (int j = 0; j < B; ++j) {
+            const int pix = (wn * B + j) * 32 + l32;
+            const int oh = oh0 + (pix >> p.log2_tw), ow = ow0 + (pix & (TW - 1));
+            const bool pix_ok = (oh < p.Ho) && (ow < p.Wo);
+            float *dst = p.ws + (((size_t)ksl * p.N + n) * p.M + (size_t)g * Mg) * HoWo + oh * p.Wo + ow;
+#pragma unroll
+            for (int i = 0; i < A; ++i)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    const int ml = m0 + wm * (32 * A) + i * 32 + 8 * (e >> 2) + 4 * lh + (e & 3);
+                    if (pix_ok && ml < Mg) dst[(size_t)ml * HoWo] = acc[i][j][e];
+                }
+        }
+        return;
+    }
+    // Bias, ReLU, one rounding to FP16; then each wave transposes its tile through LDS
+    // (2-byte writes, 16-byte reads) so that a lane holds 8 consecutive pixels of one
+    // output row and the global stores are 16, 8 or 4 bytes wide.
+    if (NSTAGE == 1) __syncthreads();            // the staging buffers are free from here on
+    constexpr int EP = 40;                       // halves per LDS row: 32 pixels + pad (80 bytes)
+    uint16_t *el = reinterpret_cast<uint16_t *>(lds) + wave * (32 * A * EP);
+    float bv[A][16];
+#pragma unroll
+    for (int i = 0; i < A; ++i)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+            const int ml = m0 + wm * (32 * A) + i * 32 + 8 * (e >> 2) + 4 * lh + (e & 3);
+            bv[i][e] = (p.bias && ml < Mg) ? (float)__builtin_bit_cast(_Float16, p.b[g * Mg + ml]) : 0.0f;
+        }
+    const int ov = p.out_vec;                    // pixels per store: divides Wo, tile_w and the base alignment
 #pragma unroll
     for (int j = 0; j < B; ++j) {
-        const int pix = (wn * B + j) * 32 + l32;
-        const int oh = oh0 + (pix >> p.log2_tw), ow = ow0 + (pix & (TW - 1));
-        const bool pix_ok = (oh < p.Ho) && (ow < p.Wo);
 #pragma unroll
-        for (int i = 0; i < A; ++i) {
+        for (int i = 0; i < A; ++i)
 #pragma unroll
             for (int e = 0; e < 16; ++e) {
-                const int ml = m0 + wm * (32 * A) + i * 32 + 8 * (e >> 2) + 4 * lh + (e & 3);
-                if (pix_ok && ml < Mg) {
-                    const int mg = g * Mg + ml;
-                    float v = acc[i][j][e];
-                    if (SPLITK) {
-                        p.ws[(((size_t)ksl * p.N + n) * p.M + mg) * HoWo + oh * p.Wo + ow] = v;
-                    } else {
-                        if (p.bias) {
-                            _Float16 hb = __builtin_bit_cast(_Float16, p.b[mg]);
-                            v += (float)hb;
-                        }
-                        if (p.relu) v = fmaxf(v, 0.0f);
-                        _Float16 hv = (_Float16)v;
-                        p.y[((size_t)n * p.M + mg) * HoWo + oh * p.Wo + ow] = __builtin_bit_cast(uint16_t, hv);
+                float v = acc[i][j][e] + bv[i][e];
+                if (p.relu) v = fmaxf(v, 0.0f);
+                const int row = i * 32 + 8 * (e >> 2) + 4 * lh + (e & 3);
+                el[row * EP + l32] = __builtin_bit_cast(uint16_t, (_Float16)v);
+            }
+#pragma unroll
+        for (int k = 0; k < 2 * A; ++k) {
+            const int id = lane + 64 * k;
+            const int row = id >> 2, chunk = id & 3;
+            const u32x4 v = *reinterpret_cast<const u32x4 *>(el + row * EP + chunk * 8);
+            const int ml = m0 + wm * (32 * A) + row;
+            if (ml >= Mg) continue;
+            uint16_t *yrow = p.y + ((size_t)n * p.M + (size_t)g * Mg + ml) * HoWo;
+            const int pix0 = (wn * B + j) * 32 + chunk * 8;
+            if (ov == 8) {
+                const int oh = oh0 + (pix0 >> p.log2_tw), ow = ow0 + (pix0 & (TW - 1));
+                if (oh < p.Ho && ow < p.Wo) *reinterpret_cast<u32x4 *>(yrow + oh * p.Wo + ow) = v;
+            } else if (ov == 4) {
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    const int pix = pix0 + 4 * h;
+                    const int oh = oh0 + (pix >> p.log2_tw), ow = ow0 + (pix & (TW - 1));
+                    if (oh < p.Ho && ow < p.Wo) {
+                        uint2 t = make_uint2(v[2 * h], v[2 * h + 1]);
+                        *reinterpret_cast<uint2 *>(yrow + oh * p.Wo + ow) = t;
                     }
+                }
+            } else if (ov == 2) {
+#pragma unroll
+                for (int h = 0; h < 4; ++h) {
+                    const int pix = pix0 + 2 * h;
+                    const int oh = oh0 + (pix >> p.log2_tw), ow = ow0 + (pix & (TW - 1));
+                    if (oh < p.Ho && ow < p.Wo) *reinterpret_cast<uint32_t *>(yrow + oh * p.Wo + ow) = v[h];
+                }
+            } else {
+#pragma unroll
+                for (int h = 0; h < 8; ++h) {
+                    const int pix = pix0 + h;
+                    const int oh = oh0 + (pix >> p.log2_tw), ow = ow0 + (pix & (TW - 1));
+                    if (oh < p.Ho && ow < p.Wo)
+                        yrow[oh * p.Wo + ow] = (uint16_t)(v[h >> 1] >> (16 * (h & 1)));
                 }
             }
         }
@@ -385,55 +519,49 @@ static hipError_t ensure_lds(Kern kern, size_t lds, std::atomic<size_t> &granted
     return e;
 }
 
-template <int KS, int A, int B, int WAVES_M, int NPL, int XVEC, bool CALIGN, int MAXR>
-static hipError_t launch_igemm(const ConvArgs &a, dim3 grid, hipStream_t stream)
+template <int KS, int A, int B, int WM, int WN, int NPL, int XVEC, bool CALIGN, int NSTAGE, int MAXR>
+static hipError_t launch_igemm(const ConvArgs &a, hipStream_t stream)
 {
-    constexpr int W_UNITS = KS * KS * NPL * 32 * A * WAVES_M;
-    const size_t lds = (size_t)(W_UNITS + NPL * a.PH * a.PWU) * 16;
+    constexpr int W_UNITS = KS * KS * NPL * 32 * A * WM;
+    size_t lds = (size_t)NSTAGE * (W_UNITS + NPL * a.PH * a.PWU) * 16;
+    lds = lds < (size_t)WM * WN * 32 * A * 80 ? (size_t)WM * WN * 32 * A * 80 : lds;   // epilogue transpose
+    const dim3 grid((unsigned)(((a.grid_blocks + 7) / 8) * 8)), block(64 * WM * WN);
     hipError_t e;
     if (a.split_k > 1) {
         static std::atomic<size_t> granted{0};
-        auto kern = igemm_kernel<KS, A, B, WAVES_M, NPL, XVEC, CALIGN, MAXR, true>;
+        auto kern = igemm_kernel<KS, A, B, WM, WN, NPL, XVEC, CALIGN, NSTAGE, MAXR, true>;
         if ((e = ensure_lds(kern, lds, granted)) != hipSuccess) return e;
-        hipLaunchKernelGGL(kern, grid, dim3(256), lds, stream, a);
+        hipLaunchKernelGGL(kern, grid, block, lds, stream, a);
     } else {
         static std::atomic<size_t> granted{0};
-        auto kern = igemm_kernel<KS, A, B, WAVES_M, NPL, XVEC, CALIGN, MAXR, false>;
+        auto kern = igemm_kernel<KS, A, B, WM, WN, NPL, XVEC, CALIGN, NSTAGE, MAXR, false>;
         if ((e = ensure_lds(kern, lds, granted)) != hipSuccess) return e;
-        hipLaunchKernelGGL(kern, grid, dim3(256), lds, stream, a);
+        hipLaunchKernelGGL(kern, grid, block, lds, stream, a);
     }
     return hipGetLastError();
 }
 
-#define HGC_VARIANT(KS, A, B, WM, NPL, XVEC, CAL, MAXR)                                        \
-    {KS, A, B, WM, NPL, XVEC, CAL, MAXR, KS * KS * NPL * 32 * A * WM * 16,                      \
-     &launch_igemm<KS, A, B, WM, NPL, XVEC, (CAL != 0), MAXR>}
+#define HGC_V1(KS, A, B, WM, WN, NPL, XVEC, CAL, NST, MAXR)                                     \
+    {KS, A, B, WM, WN, NPL, XVEC, CAL, NST, MAXR,                                               \
+     &launch_igemm<KS, A, B, WM, WN, NPL, XVEC, (CAL != 0), NST, MAXR>}
+// the four load forms of one tile shape: (vector|scalar input) x (vector|scalar weights)
+#define HGC_V4(KS, A, B, WM, WN, NPL, NST, MAXR, MAXR1)                                         \
+    HGC_V1(KS, A, B, WM, WN, NPL, 2, 1, NST, MAXR), HGC_V1(KS, A, B, WM, WN, NPL, 1, 1, NST, MAXR1),    \
+    HGC_V1(KS, A, B, WM, WN, NPL, 2, 0, NST, MAXR), HGC_V1(KS, A, B, WM, WN, NPL, 1, 0, NST, MAXR1)
 
-// For each kernel extent: vector-load and scalar-load forms of each tile shape.
 static const IgemmVariant g_variants[] = {
-    //          KS  A  B  WM NPL XVEC CAL MAXR
-    HGC_VARIANT(3, 2, 4, 2, 2, 2, 1, 3),   // 128 ch x 256 px
-    HGC_VARIANT(3, 2, 4, 2, 2, 1, 1, 3),
-    HGC_VARIANT(3, 2, 4, 2, 2, 2, 0, 3),
-    HGC_VARIANT(3, 2, 4, 2, 2, 1, 0, 3),
-    HGC_VARIANT(3, 2, 2, 1, 2, 2, 1, 3),   //  64 ch x 256 px
-    HGC_VARIANT(3, 2, 2, 1, 2, 1, 1, 3),
-    HGC_VARIANT(3, 2, 2, 1, 2, 2, 0, 3),
-    HGC_VARIANT(3, 2, 2, 1, 2, 1, 0, 3),
-    HGC_VARIANT(1, 2, 4, 2, 8, 2, 1, 4),   // pointwise: 64 channels per step
-    HGC_VARIANT(1, 2, 4, 2, 8, 1, 1, 4),
-    HGC_VARIANT(1, 2, 4, 2, 8, 2, 0, 4),
-    HGC_VARIANT(1, 2, 4, 2, 8, 1, 0, 4),
-    HGC_VARIANT(1, 2, 2, 1, 8, 2, 1, 4),
-    HGC_VARIANT(1, 2, 2, 1, 8, 1, 1, 4),
-    HGC_VARIANT(1, 2, 2, 1, 8, 2, 0, 4),
-    HGC_VARIANT(1, 2, 2, 1, 8, 1, 0, 4),
-    HGC_VARIANT(5, 2, 2, 1, 2, 2, 1, 3),
-    HGC_VARIANT(5, 2, 2, 1, 2, 1, 1, 3),
-    HGC_VARIANT(5, 2, 2, 1, 2, 2, 0, 3),
-    HGC_VARIANT(5, 2, 2, 1, 2, 1, 0, 3),
-    HGC_VARIANT(7, 1, 2, 1, 2, 2, 0, 3),   // stem-like: 32 ch x 256 px
-    HGC_VARIANT(7, 1, 2, 1, 2, 1, 0, 3),
+    //     KS  A  B  WM WN NPL NST MAXR MAXR(scalar input)
+    HGC_V4(3, 2, 4, 2, 4, 2, 2, 2, 2),    // 128 ch x 512 px, 8 waves: throughput tile
+    HGC_V4(3, 2, 4, 2, 2, 2, 2, 2, 4),    // 128 ch x 256 px
+    HGC_V4(3, 2, 2, 1, 4, 2, 2, 2, 4),    //  64 ch x 256 px
+    HGC_V4(3, 2, 2, 1, 2, 4, 2, 2, 3),    //  64 ch x 128 px, 32 channels per step: latency tile
+    HGC_V4(3, 1, 2, 1, 2, 4, 2, 2, 4),    //  32 ch x 128 px
+    HGC_V4(1, 2, 4, 2, 2, 8, 2, 2, 4),    // pointwise 128 ch x 256 px, 64 channels per step
+    HGC_V4(1, 2, 2, 1, 4, 8, 2, 2, 4),    // pointwise  64 ch x 256 px
+    HGC_V4(1, 2, 2, 1, 2, 8, 2, 2, 4),    // pointwise  64 ch x 128 px
+    HGC_V4(5, 2, 2, 1, 4, 2, 1, 3, 4),    // 5x5  64 ch x 256 px
+    HGC_V1(7, 1, 2, 1, 4, 2, 2, 0, 1, 3),   // stem-like 7x7: 32 ch x 256 px
+    HGC_V1(7, 1, 2, 1, 4, 2, 1, 0, 1, 6),
 };
 
 const IgemmVariant *igemm_variants(int *count)
