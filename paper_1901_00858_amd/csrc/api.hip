@@ -106,12 +106,14 @@ static double estimate_cycles(const Geometry &g, const Candidate &c)
     return total;
 }
 
-static bool plan_igemm(const Geometry &g, bool with_ws, bool x_al4, bool w_al16, int forced_variant,
+static bool plan_igemm(const Geometry &g, bool with_ws, int x_align, bool w_al16, int forced_variant,
                        bool force_split, Plan *pl)
 {
     int nv = 0;
     const IgemmVariant *vs = igemm_variants(&nv);
-    const int want_xvec = (g.W % 2 == 0 && x_al4) ? 2 : 1;
+    // widest input load: W and x's byte alignment / 2 must be multiples of the pixel count
+    int want_xvec = 8;
+    while (want_xvec > 1 && (g.W % want_xvec || x_align % (2 * want_xvec))) want_xvec >>= 1;
     const int want_cal = (g.Cg % 8 == 0 && w_al16) ? 1 : 0;
     Candidate best;
     best.v = nullptr;
@@ -121,9 +123,11 @@ static bool plan_igemm(const Geometry &g, bool with_ws, bool x_al4, bool w_al16,
         if (v.ks != g.k) continue;
         if (forced_variant >= 0) {
             if (i != forced_variant) continue;
-            if ((v.xvec == 2 && want_xvec != 2) || (v.calign && !want_cal)) continue;
-        } else if (v.xvec != want_xvec || v.calign != want_cal) {
-            continue;
+            if (v.xvec > want_xvec || (v.calign && !want_cal)) continue;
+        } else {
+            // ragged-channel forms exist for 2- and 1-pixel loads only
+            const int xv = want_cal ? want_xvec : std::min(want_xvec, 2);
+            if (v.xvec != xv || v.calign != want_cal) continue;
         }
         const int BN = v.BN();
         for (int j = 2; (1 << j) <= BN && j <= 6; ++j) {
@@ -136,8 +140,9 @@ static bool plan_igemm(const Geometry &g, bool with_ws, bool x_al4, bool w_al16,
             c.tiles_m = ceil_div(g.Mg, v.BM());
             c.PH = (TH - 1) * g.s + g.k;
             const int PW = (TW - 1) * g.s + g.k;
-            c.PWU = (v.xvec == 2) ? 2 * ((PW + 2) / 2) : PW;
-            c.lds = std::max(v.nstage * (v.w_lds_bytes() + 16LL * v.npl * c.PH * c.PWU), v.epilogue_lds_bytes());
+            // units per patch row: PW pixels starting up to xvec-1 pixels after an aligned column
+            c.PWU = ((PW + v.xvec - 1 + v.xvec - 1) / v.xvec) * v.xvec;
+            c.lds = v.lds_bytes(c.PH, c.PWU);
             if (c.lds > kMaxLds) continue;
             c.nsteps = ceil_div(g.Cg, 8 * v.npl);
             c.grid = (long long)c.tiles_m * c.tiles_w * c.tiles_h * g.G * g.N;
@@ -174,7 +179,7 @@ static bool plan_igemm(const Geometry &g, bool with_ws, bool x_al4, bool w_al16,
     return true;
 }
 
-static void make_plan(const Geometry &g, bool with_ws, bool x_al4, bool w_al16, Plan *pl)
+static void make_plan(const Geometry &g, bool with_ws, int x_align, bool w_al16, Plan *pl)
 {
     std::memset(pl, 0, sizeof(*pl));
     base_args(g, &pl->args);
@@ -198,7 +203,7 @@ static void make_plan(const Geometry &g, bool with_ws, bool x_al4, bool w_al16, 
     }
     if (path == HGC_PATH_IGEMM || path == HGC_PATH_IGEMM_SPLITK) {
         const bool ws = with_ws && (forced != HGC_PATH_IGEMM);
-        if (plan_igemm(g, ws, x_al4, w_al16, fvar, forced == HGC_PATH_IGEMM_SPLITK && with_ws, pl))
+        if (plan_igemm(g, ws, x_align, w_al16, fvar, forced == HGC_PATH_IGEMM_SPLITK && with_ws, pl))
             return;
         base_args(g, &pl->args);
     }
@@ -216,9 +221,10 @@ static hgc_status run(const hgc_conv2d_desc *desc, const void *x, const void *w,
     hgc_status st = validate(desc, &g);
     if (st != HGC_OK) return st;
     Plan pl;
-    const bool x_al4 = ((uintptr_t)x & 3) == 0;
+    int x_align = 16;                            // byte alignment of x, capped at 16
+    while (x_align > 2 && ((uintptr_t)x % x_align)) x_align >>= 1;
     const bool w_al16 = ((uintptr_t)w & 15) == 0;
-    make_plan(g, with_ws, x_al4, w_al16, &pl);
+    make_plan(g, with_ws, x_align, w_al16, &pl);
     if (pl.pub.workspace_bytes > 0) {
         // the size reported to the caller assumed aligned tensors; an unaligned call
         // may need the same or less, never more (same tiles, same split rule)
@@ -230,6 +236,8 @@ static hgc_status run(const hgc_conv2d_desc *desc, const void *x, const void *w,
     a.b = static_cast<const uint16_t *>(b);
     a.y = static_cast<uint16_t *>(y);
     a.ws = static_cast<float *>(ws);
+    a.x_bytes = (uint32_t)(2LL * g.N * g.C * g.H * g.W);
+    a.w_bytes = (uint32_t)(2LL * g.M * g.Kg);
     {   // widest output store: divides Wo and the window width, and y's byte alignment allows it
         int ov = 8;
         while (ov > 1 && (g.Wo % ov || (1 << a.log2_tw) % ov || ((uintptr_t)y % (2 * ov)))) ov >>= 1;
@@ -243,7 +251,7 @@ static hgc_status run(const hgc_conv2d_desc *desc, const void *x, const void *w,
         break;
     case HGC_PATH_IGEMM:
     case HGC_PATH_IGEMM_SPLITK:
-        e = pl.variant->launch(a, s);
+        e = pl.variant->launch(a, (size_t)pl.pub.lds_bytes, s);
         if (e == hipSuccess && a.split_k > 1) e = launch_splitk_reduce(a, s);
         break;
     default:
@@ -280,16 +288,15 @@ hgc_status hgc_conv2d_workspace_size(const hgc_conv2d_desc *desc, size_t *bytes_
     hgc_status st = validate(desc, &g);
     if (st != HGC_OK) return st;
     Plan pl;
-    make_plan(g, true, true, true, &pl);
+    make_plan(g, true, 16, true, &pl);
     long long need = pl.pub.workspace_bytes;
-    // an unaligned tensor base selects a different instantiation with its own tiles
-    Plan alt;
-    make_plan(g, true, false, false, &alt);
-    if (alt.pub.workspace_bytes > need) need = alt.pub.workspace_bytes;
-    make_plan(g, true, true, false, &alt);
-    if (alt.pub.workspace_bytes > need) need = alt.pub.workspace_bytes;
-    make_plan(g, true, false, true, &alt);
-    if (alt.pub.workspace_bytes > need) need = alt.pub.workspace_bytes;
+    // a less aligned tensor base selects a different instantiation with its own tiles
+    for (int xa = 2; xa <= 16; xa *= 2)
+        for (int wa = 0; wa < 2; ++wa) {
+            Plan alt;
+            make_plan(g, true, xa, wa != 0, &alt);
+            if (alt.pub.workspace_bytes > need) need = alt.pub.workspace_bytes;
+        }
     *bytes_out = (size_t)need;
     return HGC_OK;
 }
@@ -301,7 +308,7 @@ hgc_status hgc_conv2d_plan(const hgc_conv2d_desc *desc, int32_t with_workspace, 
     hgc_status st = validate(desc, &g);
     if (st != HGC_OK) return st;
     Plan pl;
-    make_plan(g, with_workspace != 0, true, true, &pl);
+    make_plan(g, with_workspace != 0, 16, true, &pl);
     *plan_out = pl.pub;
     return HGC_OK;
 }

@@ -34,11 +34,23 @@ struct ConvArgs {
     int tiles_w, tiles_h, tiles_m;
     int PH, PWU;         // input halo patch: rows, and 16-byte units (pixels) per row
     int nsteps;          // channel blocks of CB channels per group: ceil(Cg / CB)
+    uint32_t x_bytes;    // size of x and w in bytes (buffer-load range checks)
+    uint32_t w_bytes;
     int out_vec;         // output pixels per store (8, 4, 2 or 1): divides Wo and tile_w, fits y's alignment
     int grid_blocks;     // workgroups that have work (the launch pads to a multiple of 8)
     int split_k;         // reduction slices (1 = none)
     int steps_per_split; // channel blocks per slice
 };
+
+// LDS units (16 bytes) of one weight buffer: every wave owns a slice that holds
+// its BM/NW rows, rounded up so that each lane of each 64-lane load round lands inside.
+constexpr int igemm_w_units(int ks, int wm_blocks, int waves_m, int waves_n, int npl)
+{
+    const int nw = waves_m * waves_n;
+    const int rpw = 32 * wm_blocks * waves_m / nw;
+    const int wch = rpw * npl * ks * ks;
+    return nw * ((wch + 63) / 64) * 64;
+}
 
 // One instantiation of the implicit-GEMM kernel.
 struct IgemmVariant {
@@ -52,12 +64,17 @@ struct IgemmVariant {
     int calign;          // 1: Cg % 8 == 0, weights fetched as 16-byte vectors
     int nstage;          // LDS buffers (2 = double buffered)
     int max_rounds;      // patch staging rounds pipelined through registers
-    hipError_t (*launch)(const ConvArgs &, hipStream_t stream);
+    hipError_t (*launch)(const ConvArgs &, size_t lds_bytes, hipStream_t stream);
     int BM() const { return 32 * wm_blocks * waves_m; }
     int BN() const { return 32 * wn_blocks * waves_n; }
     int threads() const { return 64 * waves_m * waves_n; }
-    long long w_lds_bytes() const { return 16LL * ks * ks * npl * BM(); }
-    long long epilogue_lds_bytes() const { return 80LL * 32 * wm_blocks * waves_m * waves_n; }
+    // LDS of a launch: stages of {weights, patch + 8 dump units}; the epilogue reuses it
+    long long lds_bytes(int PH, int PWU) const
+    {
+        const long long stage = 16LL * (igemm_w_units(ks, wm_blocks, waves_m, waves_n, npl) + npl * PH * PWU + 8);
+        const long long epi = 80LL * 32 * wm_blocks * waves_m * waves_n;
+        return nstage * stage > epi ? nstage * stage : epi;
+    }
 };
 
 const IgemmVariant *igemm_variants(int *count);

@@ -18,16 +18,21 @@
 // underflow arise during accumulation); bias, ReLU and the single FP32->FP16
 // rounding happen in registers before the store (no conversion pass, Section 3.3).
 //
-// Staging.  Input: each item is XVEC pixels x 8 channels; eight coalesced loads
-// (one per channel plane of NCHW) are transposed in registers with v_perm_b32
-// into XVEC 16-byte units.  Weights: each wave owns BM/NW rows; it fetches their
-// contiguous CB*k*k-half runs with coalesced 16-byte LDS-direct loads
-// (global_load_lds_dwordx4) into its own slice of the LDS weight buffer, reads
-// them back one (row, plane) per lane and writes the regrouped units over the
-// same slice (LDS operations of one wave execute in order, so no barrier is
-// needed inside the wave).
+// Staging is branch-free so that a whole K step is one basic block the scheduler
+// can interleave with the MFMAs.  All global reads are buffer loads: a lane's
+// byte offset is fixed for the kernel, the step only moves a scalar offset, and an
+// offset of ~0 (padding pixel, channel or row outside the problem) makes the
+// hardware return zero instead of a predicate.
+//   Input: each item is XVEC pixels x 8 channels; eight loads (one per channel
+// plane of NCHW, coalesced along W) are transposed in registers with v_perm_b32
+// into XVEC units.  Items past the end of the patch write a dump unit.
+//   Weights: each wave owns BM/NW rows; it fetches their contiguous CB*k*k-half
+// runs with 16-byte LDS-direct loads (buffer_load_dwordx4 ... lds) into its own
+// slice of the LDS weight buffer, reads them back one (row, plane) per lane and
+// writes the regrouped units over the same slice.  LDS operations of one wave
+// execute in order, so no barrier is needed inside the wave.
 // With NSTAGE = 2 the LDS buffers are double: the loads of step s+1 are issued
-// before the MFMAs of step s and land in the other buffer half-way through them.
+// before the MFMAs of step s and are stored to the other buffer after them.
 #include <atomic>
 
 #include "hgc_internal.h"
@@ -37,6 +42,9 @@ namespace hgc {
 typedef _Float16 half8 __attribute__((ext_vector_type(8)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) void *lds_ptr_t;
+
+constexpr uint32_t kNoLoad = 0xFFFFFFFFu;       // buffer offset that is always out of range
 
 __device__ __forceinline__ uint32_t pack_lo(uint32_t a, uint32_t b)   // a.lo | b.lo << 16
 {
@@ -47,83 +55,105 @@ __device__ __forceinline__ uint32_t pack_hi(uint32_t a, uint32_t b)   // a.hi | 
     return __builtin_amdgcn_perm(b, a, 0x07060302u);
 }
 
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void *base, uint32_t bytes)
+{
+    // raw buffer, stride 0, 32-bit data format: offsets >= bytes read as zero
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, bytes, 0x00020000);
+}
+
 // Decoded staging item of the input patch: XVEC pixels x 8 channels.
 struct PatchItem {
-    int goff;    // element offset of (channel 0 of the plane, pixel) from the channel-block base
-    int unit;    // LDS unit index of the first pixel
-    int pl8;     // first channel of the plane within the block (plane * 8)
-    int flags;   // bit0: item exists, bit1: pixel(s) inside the image
+    uint32_t voff;   // byte offset of (channel 0 of the plane, first pixel) in x at K step 0, or kNoLoad
+    int unit;        // LDS unit index of the first pixel (the dump unit for items past the end)
+    int pl8;         // first channel of the plane within a channel block (plane * 8)
 };
 
 template <int XVEC>
 __device__ __forceinline__ PatchItem decode_patch_item(int id, int total, int ipr, int PH, int PWU,
-                                                       int ih0, int iwa, int H, int W, int HW)
+                                                       int ih0, int iwa, int H, int W, int HW,
+                                                       uint32_t plane0_off, int dump_unit)
 {
     PatchItem it;
-    int pd = id % ipr;
-    int t = id / ipr;
-    int ph = t % PH;
-    int pl = t / PH;
-    int ih = ih0 + ph;
-    int iw = iwa + pd * XVEC;
-    bool active = id < total;
-    bool inside = active && ih >= 0 && ih < H && iw >= 0 && iw < W;
-    it.goff = pl * 8 * HW + ih * W + iw;
-    it.unit = (pl * PH + ph) * PWU + pd * XVEC;
+    const int pd = id % ipr;
+    const int t = id / ipr;
+    const int ph = t % PH;
+    const int pl = t / PH;
+    const int ih = ih0 + ph;
+    const int iw = iwa + pd * XVEC;
+    const bool active = id < total;
+    const bool inside = active && ih >= 0 && ih < H && iw >= 0 && iw < W;
+    it.voff = inside ? plane0_off + 2u * (uint32_t)(pl * 8 * HW + ih * W + iw) : kNoLoad;
+    it.unit = active ? (pl * PH + ph) * PWU + pd * XVEC : dump_unit;
     it.pl8 = pl * 8;
-    it.flags = (active ? 1 : 0) | (inside ? 2 : 0);
     return it;
 }
 
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+// XVEC pixels (XVEC*2 bytes) of each of the 8 channels of the item's plane.
+// d[j][k]: channel j, dword k (two pixels per dword; one pixel when XVEC == 1).
 template <int XVEC, bool CALIGN>
-__device__ __forceinline__ void load_patch_item(const uint16_t *xcb, const PatchItem &it, int c0,
-                                                int Cg, int HW, uint32_t (&d)[8])
+__device__ __forceinline__ void load_patch_item(__amdgpu_buffer_rsrc_t rx, const PatchItem &it, int c0,
+                                                int Cg, uint32_t soff, uint32_t chan_bytes,
+                                                uint32_t (&d)[8][(XVEC + 1) / 2])
 {
-    const bool inside = (it.flags & 2) != 0;
-    if (CALIGN) {
-        const bool ok = inside && (c0 + it.pl8 < Cg);
+    const uint32_t vplane = (c0 + it.pl8 < Cg) ? it.voff : kNoLoad;
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            uint32_t v = 0;
-            if (ok) {
-                if (XVEC == 2) v = *reinterpret_cast<const uint32_t *>(xcb + it.goff + j * HW);
-                else v = xcb[it.goff + j * HW];
-            }
-            d[j] = v;
-        }
-    } else {
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            uint32_t v = 0;
-            if (inside && (c0 + it.pl8 + j < Cg)) {
-                if (XVEC == 2) v = *reinterpret_cast<const uint32_t *>(xcb + it.goff + j * HW);
-                else v = xcb[it.goff + j * HW];
-            }
-            d[j] = v;
+    for (int j = 0; j < 8; ++j) {
+        const uint32_t vo = CALIGN ? vplane : ((c0 + it.pl8 + j < Cg) ? it.voff : kNoLoad);
+        const uint32_t so = soff + j * chan_bytes;
+        if (XVEC == 8) {
+            const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rx, vo, so, 0);
+            d[j][0] = v.x; d[j][1 % ((XVEC + 1) / 2)] = v.y; d[j][2 % ((XVEC + 1) / 2)] = v.z; d[j][3 % ((XVEC + 1) / 2)] = v.w;
+        } else if (XVEC == 4) {
+            const u32x2 v = __builtin_amdgcn_raw_buffer_load_b64(rx, vo, so, 0);
+            d[j][0] = v.x; d[j][1 % ((XVEC + 1) / 2)] = v.y;
+        } else if (XVEC == 2) {
+            d[j][0] = __builtin_amdgcn_raw_buffer_load_b32(rx, vo, so, 0);
+        } else {
+            d[j][0] = (uint16_t)__builtin_amdgcn_raw_buffer_load_b16(rx, vo, so, 0);
         }
     }
 }
 
+// Transpose 8 channels x XVEC pixels into XVEC units of 8 channels.
 template <int XVEC>
-__device__ __forceinline__ void store_patch_item(u32x4 *xl, const PatchItem &it, const uint32_t (&d)[8])
+__device__ __forceinline__ void store_patch_item(u32x4 *xl, const PatchItem &it,
+                                                 const uint32_t (&d)[8][(XVEC + 1) / 2])
 {
-    if (!(it.flags & 1)) return;
-    u32x4 u0;
-    u0.x = pack_lo(d[0], d[1]); u0.y = pack_lo(d[2], d[3]);
-    u0.z = pack_lo(d[4], d[5]); u0.w = pack_lo(d[6], d[7]);
-    xl[it.unit] = u0;
-    if (XVEC == 2) {
-        u32x4 u1;
-        u1.x = pack_hi(d[0], d[1]); u1.y = pack_hi(d[2], d[3]);
-        u1.z = pack_hi(d[4], d[5]); u1.w = pack_hi(d[6], d[7]);
-        xl[it.unit + 1] = u1;
+#pragma unroll
+    for (int px = 0; px < XVEC; ++px) {
+        const int k = px >> 1;
+        u32x4 u;
+        if (px & 1) {
+            u.x = pack_hi(d[0][k], d[1][k]); u.y = pack_hi(d[2][k], d[3][k]);
+            u.z = pack_hi(d[4][k], d[5][k]); u.w = pack_hi(d[6][k], d[7][k]);
+        } else {
+            u.x = pack_lo(d[0][k], d[1][k]); u.y = pack_lo(d[2][k], d[3][k]);
+            u.z = pack_lo(d[4][k], d[5][k]); u.w = pack_lo(d[6][k], d[7][k]);
+        }
+        xl[it.unit + px] = u;
+    }
+}
+
+// Scheduling hints for a region that mixes MFMAs with staging work: one MFMA, then
+// up to NV vector-memory, ND LDS and NA VALU instructions, N times.
+template <int N, int NV, int ND, int NA>
+__device__ __forceinline__ void interleave_hint()
+{
+#pragma unroll
+    for (int i = 0; i < N; ++i) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        if (NV) __builtin_amdgcn_sched_group_barrier(0x020, NV, 0);
+        if (ND) __builtin_amdgcn_sched_group_barrier(0x300, ND, 0);
+        if (NA) __builtin_amdgcn_sched_group_barrier(0x002, NA, 0);
     }
 }
 
 // KS: kernel extent.  A, B: 32x32 accumulator blocks per wave along channels and
 // pixels.  WAVES_M x WAVES_N waves per workgroup.  NPL: 8-channel planes per K
-// step.  XVEC: input pixels per global load (2 needs even W and a 4-byte aligned
-// base).  CALIGN: Cg % 8 == 0 and a 16-byte aligned weight base.  NSTAGE: LDS
+// step.  XVEC: input pixels per global load (1, 2, 4 or 8; W and the byte alignment
+// of x must be multiples of it).  CALIGN: Cg % 8 == 0 and a 16-byte aligned weight base.  NSTAGE: LDS
 // buffers (1 or 2).  MAXR: patch staging rounds held in registers.  SPLITK: write
 // FP32 partial sums of a slice of the channel blocks instead of the output.
 template <int KS, int A, int B, int WAVES_M, int WAVES_N, int NPL, int XVEC, bool CALIGN, int NSTAGE,
@@ -136,20 +166,23 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void igemm_kernel(const Con
     constexpr int BN = 32 * B * WAVES_N;
     constexpr int T = KS * KS;
     constexpr int CB = 8 * NPL;
-    constexpr int W_UNITS = T * NPL * BM;
     constexpr int RPW = BM / NW;                 // weight rows staged by one wave
     constexpr int CPR = NPL * T;                 // 16-byte chunks per row per step
-    constexpr int WCH = RPW * CPR;               // chunks (= LDS units) per wave
-    constexpr int WLR = (WCH + 63) / 64;         // load rounds per lane
+    constexpr int WCH = RPW * CPR;               // chunks (= LDS units) of one wave's rows
+    constexpr int WLR = (WCH + 63) / 64;         // LDS-direct load rounds per lane
+    constexpr int WSL = WLR * 64;                // LDS units of one wave's slice (every lane of every round lands inside)
+    constexpr int W_UNITS = NW * WSL;
     constexpr int WIT = RPW * NPL;               // (row, plane) items per wave
     constexpr int WIR = (WIT + 63) / 64;
-    constexpr bool WPREFETCH = CALIGN;
+    constexpr int TC = T < 9 ? T : 9;            // taps handled together by the scalar weight path
     static_assert(NPL % 2 == 0, "planes come in pairs (16 channels per MFMA)");
     static_assert(BM % NW == 0 && (RPW & (RPW - 1)) == 0, "rows per wave must be a power of two");
+    static_assert(W_UNITS == igemm_w_units(KS, A, WAVES_M, WAVES_N, NPL), "host and kernel disagree on LDS");
 
     extern __shared__ u32x4 lds[];
-    const int X_UNITS = NPL * p.PH * p.PWU;
-    const int stage_units = W_UNITS + X_UNITS;   // [stage]{ W[wave][T][NPL][RPW] , X[NPL][PH][PWU] }
+    const int X_UNITS = NPL * p.PH * p.PWU + 8;  // + dump units (one item's worth) for staging items past the end
+    const int stage_units = W_UNITS + X_UNITS;   // [stage]{ W[wave]{[T][NPL][RPW]} , X[NPL][PH][PWU], dump }
+    const int dump_unit = X_UNITS - 8;
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -182,139 +215,141 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void igemm_kernel(const Con
     const int s = p.stride;
     const int ih0 = oh0 * s - p.pad;
     const int iw0 = ow0 * s - p.pad;
-    const int iwa = (XVEC == 2) ? (iw0 & ~1) : iw0;
+    const int iwa = iw0 & ~(XVEC - 1);           // aligned start of the patch rows (two's complement floor)
     const int cofs = iw0 - iwa;
     const int PH = p.PH, PWU = p.PWU;
     const int HW = p.H * p.W;
     const int Cg = p.Cg, Mg = p.Mg;
 
+    const __amdgpu_buffer_rsrc_t rx = make_rsrc(p.x, p.x_bytes);
+    const __amdgpu_buffer_rsrc_t rw = make_rsrc(p.w, p.w_bytes);
+
     // ---- staging maps (do not depend on the K step) ----
     const int ipr = PWU / XVEC;                  // items per patch row
     const int total_items = NPL * PH * ipr;
     const int rounds = (total_items + NT - 1) / NT;
+    const uint32_t plane0_off = 2u * (uint32_t)((n * p.C + g * Cg) * HW);   // elements < 2^31: fits
+    const uint32_t chan_bytes = 2u * (uint32_t)HW;
     PatchItem pit[MAXR];
 #pragma unroll
     for (int r = 0; r < MAXR; ++r)
-        pit[r] = decode_patch_item<XVEC>(r * NT + tid, total_items, ipr, PH, PWU, ih0, iwa, p.H, p.W, HW);
-
-    const uint16_t *xg = p.x + ((size_t)n * p.C + (size_t)g * Cg) * HW;
-    const uint16_t *wg = p.w + (size_t)g * Mg * Cg * T;
-
-    uint32_t xreg[MAXR][8];
+        pit[r] = decode_patch_item<XVEC>(r * NT + tid, total_items, ipr, PH, PWU, ih0, iwa, p.H, p.W, HW,
+                                         plane0_off, dump_unit);
+    uint32_t xreg[MAXR][8][(XVEC + 1) / 2];
 
     auto load_x = [&](int st) {
-        const uint16_t *xcb = xg + (size_t)st * CB * HW;
+        const uint32_t soff = (uint32_t)(st * CB) * chan_bytes;
 #pragma unroll
         for (int r = 0; r < MAXR; ++r)
-            load_patch_item<XVEC, CALIGN>(xcb, pit[r], st * CB, Cg, HW, xreg[r]);
+            load_patch_item<XVEC, CALIGN>(rx, pit[r], st * CB, Cg, soff, chan_bytes, xreg[r]);
     };
     auto store_x = [&](int st, u32x4 *xl) {
 #pragma unroll
         for (int r = 0; r < MAXR; ++r) store_patch_item<XVEC>(xl, pit[r], xreg[r]);
         // patches larger than the register capacity: remaining rounds, not pipelined
         if (rounds > MAXR) {
-            const uint16_t *xcb = xg + (size_t)st * CB * HW;
+            const uint32_t soff = (uint32_t)(st * CB) * chan_bytes;
             for (int r = MAXR; r < rounds; ++r) {
-                PatchItem it = decode_patch_item<XVEC>(r * NT + tid, total_items, ipr, PH, PWU,
-                                                       ih0, iwa, p.H, p.W, HW);
-                uint32_t d[8];
-                load_patch_item<XVEC, CALIGN>(xcb, it, st * CB, Cg, HW, d);
+                PatchItem it = decode_patch_item<XVEC>(r * NT + tid, total_items, ipr, PH, PWU, ih0, iwa,
+                                                       p.H, p.W, HW, plane0_off, dump_unit);
+                uint32_t d[8][(XVEC + 1) / 2];
+                load_patch_item<XVEC, CALIGN>(rx, it, st * CB, Cg, soff, chan_bytes, d);
                 store_patch_item<XVEC>(xl, it, d);
             }
         }
     };
 
     // ---- weights ----
-    // Raw rows go from global memory straight into this wave's slice of an LDS weight
-    // buffer (global_load_lds, 16 bytes per lane, consecutive lanes -> consecutive
-    // units); rows or planes outside the problem are fetched from a valid dummy
-    // address and zeroed when they are regrouped.
-    int wofs[WPREFETCH ? WLR : 1];
-    if (WPREFETCH) {
+    const uint32_t wgrp_off = 2u * (uint32_t)(g * Mg * Cg * T);           // M*Kg < 2^31: fits
+    uint32_t wvoff[CALIGN ? WLR : 1];            // byte offset of (row, chunk) at K step 0
+    int wpl8[CALIGN ? WLR : 1];
+    if (CALIGN) {
 #pragma unroll
         for (int k = 0; k < WLR; ++k) {
             const int id = lane + 64 * k;
             const int row = id / CPR, j = id % CPR;
             const int m = m0 + wave * RPW + row;
-            // -1: row outside the problem; plane validity depends on the step
-            wofs[k] = (id < WCH && m < Mg) ? (m * Cg * T + j * 8) : -1;
+            wvoff[k] = (id < WCH && m < Mg) ? wgrp_off + 2u * (uint32_t)(m * Cg * T + j * 8) : kNoLoad;
+            wpl8[k] = (j / T) * 8;
         }
     }
     auto load_w = [&](int st, u32x4 *wl) {
-        if (!WPREFETCH) return;
-        u32x4 *mine = wl + wave * WCH;
+        if (!CALIGN) return;
+        u32x4 *mine = wl + wave * WSL;
+        const uint32_t soff = 2u * (uint32_t)(st * CB * T);
 #pragma unroll
         for (int k = 0; k < WLR; ++k) {
-            const int id = lane + 64 * k;
-            const int j = id % CPR;
-            const bool ok = (wofs[k] >= 0) && (st * CB + (j / T) * 8 < Cg);
-            const uint16_t *src = ok ? (wg + (size_t)wofs[k] + (size_t)st * CB * T) : wg;
-            if (id < WCH)
-                __builtin_amdgcn_global_load_lds(
-                    (const __attribute__((address_space(1))) void *)src,
-                    (__attribute__((address_space(3))) void *)(mine + 64 * k), 16, 0, 0);
+            const uint32_t vo = (st * CB + wpl8[k] < Cg) ? wvoff[k] : kNoLoad;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rw, (lds_ptr_t)(mine + 64 * k), 16, vo, soff, 0, 0);
         }
     };
-    auto store_w = [&](int st, u32x4 *wl) {
-        u32x4 *mine = wl + wave * WCH;           // this wave's slice: final layout [T][NPL][RPW]
-        if (WPREFETCH) {
+    // regroup items: lanes past the item count redo item (lane % WIT) and write the dump unit
+    auto store_w = [&](int st, u32x4 *wl, u32x4 *xl) {
+        u32x4 *mine = wl + wave * WSL;           // this wave's slice: final layout [T][NPL][RPW]
+        if (CALIGN) {
             // the raw rows ([row][CPR] chunks) have landed (caller waited on vmcnt);
             // read back one (row, plane) per lane: halves e = c*T + tap, c = 0..7 ...
             u32x4 rr[WIR][T];
 #pragma unroll
             for (int k = 0; k < WIR; ++k) {
-                const int item = lane + 64 * k;
+                const int item = (lane + 64 * k) % WIT;
                 const int row = item % RPW, pl = item / RPW;
-                if (item < WIT) {
 #pragma unroll
-                    for (int t = 0; t < T; ++t) rr[k][t] = mine[row * CPR + pl * T + t];
-                }
+                for (int t = 0; t < T; ++t) rr[k][t] = mine[row * CPR + pl * T + t];
             }
             // ... and write one unit per tap: the 8 channels of (row, tap)
 #pragma unroll
             for (int k = 0; k < WIR; ++k) {
-                const int item = lane + 64 * k;
+                const bool real = (WIT % 64 == 0) || (lane + 64 * k < WIT);
+                const int item = (lane + 64 * k) % WIT;
                 const int row = item % RPW, pl = item / RPW;
-                if (item < WIT) {
-                    const bool ok = (m0 + wave * RPW + row < Mg) && (st * CB + pl * 8 < Cg);
+                const bool ok = (m0 + wave * RPW + row < Mg) && (st * CB + pl * 8 < Cg);
+                u32x4 *dst = real ? mine + pl * RPW + row : xl + dump_unit;
+                const int tstride = real ? NPL * RPW : 0;
 #pragma unroll
-                    for (int t = 0; t < T; ++t) {
-                        uint32_t o[4];
+                for (int t = 0; t < T; ++t) {
+                    uint32_t o[4];
 #pragma unroll
-                        for (int i = 0; i < 4; ++i) {
-                            const int ea = (2 * i) * T + t, eb = (2 * i + 1) * T + t;
-                            const int da = ea >> 1, db = eb >> 1;
-                            const uint32_t va = rr[k][da >> 2][da & 3];
-                            const uint32_t vb = rr[k][db >> 2][db & 3];
-                            const uint32_t sel = ((ea & 1) ? 0x0302u : 0x0100u) |
-                                                 (((eb & 1) ? 0x0706u : 0x0504u) << 16);
-                            o[i] = ok ? __builtin_amdgcn_perm(vb, va, sel) : 0u;
-                        }
-                        u32x4 u = {o[0], o[1], o[2], o[3]};
-                        mine[(t * NPL + pl) * RPW + row] = u;
+                    for (int i = 0; i < 4; ++i) {
+                        const int ea = (2 * i) * T + t, eb = (2 * i + 1) * T + t;
+                        const int da = ea >> 1, db = eb >> 1;
+                        const uint32_t va = rr[k][da >> 2][da & 3];
+                        const uint32_t vb = rr[k][db >> 2][db & 3];
+                        const uint32_t sel = ((ea & 1) ? 0x0302u : 0x0100u) |
+                                             (((eb & 1) ? 0x0706u : 0x0504u) << 16);
+                        o[i] = ok ? __builtin_amdgcn_perm(vb, va, sel) : 0u;
                     }
+                    u32x4 u = {o[0], o[1], o[2], o[3]};
+                    dst[t * tstride] = u;
                 }
             }
         } else {
-            // any Cg, any alignment: 2-byte loads straight into the final layout
+            // any Cg, any alignment: 2-byte buffer loads straight into the final layout
             for (int k = 0; k < WIR; ++k) {
-                const int item = lane + 64 * k;
-                if (item >= WIT) continue;
+                const bool real = (WIT % 64 == 0) || (lane + 64 * k < WIT);
+                const int item = (lane + 64 * k) % WIT;
                 const int row = item % RPW, pl = item / RPW;
                 const int m = m0 + wave * RPW + row;
                 const int c0 = st * CB + pl * 8;
-                const uint16_t *src = wg + ((size_t)m * Cg + c0) * T;
-                for (int t = 0; t < T; ++t) {
-                    uint32_t h[8];
+                const uint32_t vrow = (real && m < Mg) ? wgrp_off + 2u * (uint32_t)((m * Cg + c0) * T) : kNoLoad;
+                u32x4 *dst = real ? mine + pl * RPW + row : xl + dump_unit;
+                const int tstride = real ? NPL * RPW : 0;
+                for (int t0 = 0; t0 < T; t0 += TC) {
+                    uint32_t h[TC][8];
 #pragma unroll
-                    for (int j = 0; j < 8; ++j) {
-                        uint32_t v = 0;
-                        if (m < Mg && (c0 + j < Cg)) v = src[j * T + t];
-                        h[j] = v;
+                    for (int tt = 0; tt < TC; ++tt)
+#pragma unroll
+                        for (int j = 0; j < 8; ++j) {
+                            const uint32_t vo = (c0 + j < Cg && t0 + tt < T) ? vrow : kNoLoad;
+                            h[tt][j] = (uint16_t)__builtin_amdgcn_raw_buffer_load_b16(
+                                rw, vo, 2u * (uint32_t)(j * T + t0 + tt), 0);
+                        }
+#pragma unroll
+                    for (int tt = 0; tt < TC; ++tt) {
+                        u32x4 u = {h[tt][0] | (h[tt][1] << 16), h[tt][2] | (h[tt][3] << 16),
+                                   h[tt][4] | (h[tt][5] << 16), h[tt][6] | (h[tt][7] << 16)};
+                        if (t0 + tt < T) dst[(t0 + tt) * tstride] = u;
                     }
-                    u32x4 u = {h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16),
-                               h[6] | (h[7] << 16)};
-                    mine[(t * NPL + pl) * RPW + row] = u;
                 }
             }
         }
@@ -332,7 +367,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void igemm_kernel(const Con
 #pragma unroll
     for (int i = 0; i < A; ++i) {
         const int m = wm * (32 * A) + i * 32 + l32;
-        ab[i] = (m / RPW) * WCH + lh * RPW + (m % RPW);
+        ab[i] = (m / RPW) * WSL + lh * RPW + (m % RPW);
     }
     const int plane_pair_stride = 2 * PH * PWU;
 
@@ -344,30 +379,37 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void igemm_kernel(const Con
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
 
-    auto compute = [&](const u32x4 *wl, const u32x4 *xl, int t0, int t1) {
-#pragma unroll
-        for (int t = 0; t < T; ++t) {
-            if (t < t0 || t >= t1) continue;
+    // One K step: T taps x NPL/2 plane pairs.  Fragments are double-buffered in
+    // registers: the ds_reads of iteration it+1 are issued before the MFMAs of
+    // iteration it, so their latency hides behind A*B MFMAs.
+    auto compute = [&](const u32x4 *wl, const u32x4 *xl, int it0, int it1) {
+        constexpr int NIT = T * (NPL / 2);
+        half8 af[2][A], bf[2][B];
+        auto frag_load = [&](int it, half8 (&fa)[A], half8 (&fb)[B]) {
+            const int t = it / (NPL / 2), pp = it % (NPL / 2);
             const int r = t / KS, q = t % KS;
-            const int toff = r * PWU + q;
+            const int toff = r * PWU + q + pp * plane_pair_stride;
 #pragma unroll
-            for (int pp = 0; pp < NPL / 2; ++pp) {
-                half8 af[A], bf[B];
+            for (int i = 0; i < A; ++i)
+                fa[i] = __builtin_bit_cast(half8, wl[ab[i] + (t * NPL + pp * 2) * RPW]);
 #pragma unroll
-                for (int i = 0; i < A; ++i)
-                    af[i] = __builtin_bit_cast(half8, wl[ab[i] + (t * NPL + pp * 2) * RPW]);
+            for (int j = 0; j < B; ++j) fb[j] = __builtin_bit_cast(half8, xl[xb[j] + toff]);
+        };
+        frag_load(it0, af[it0 & 1], bf[it0 & 1]);
+#pragma unroll
+        for (int it = 0; it < NIT; ++it) {
+            if (it < it0 || it >= it1) continue;
+            if (it + 1 < it1) frag_load(it + 1, af[(it + 1) & 1], bf[(it + 1) & 1]);
+#pragma unroll
+            for (int i = 0; i < A; ++i)
 #pragma unroll
                 for (int j = 0; j < B; ++j)
-                    bf[j] = __builtin_bit_cast(half8, xl[xb[j] + toff + pp * plane_pair_stride]);
-#pragma unroll
-                for (int i = 0; i < A; ++i)
-#pragma unroll
-                    for (int j = 0; j < B; ++j)
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af[i], bf[j], acc[i][j], 0, 0, 0);
-            }
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af[it & 1][i], bf[it & 1][j],
+                                                                       acc[i][j], 0, 0, 0);
         }
     };
-
+    constexpr int NIT_ALL = T * (NPL / 2);
+    constexpr int NIT_H = (NIT_ALL + 1) / 2;
     // ---- K loop over channel blocks ----
     int st0 = 0, st1 = p.nsteps;
     if (SPLITK) {
@@ -377,45 +419,45 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void igemm_kernel(const Con
     // all outstanding vector-memory operations (patch loads and LDS-direct weight rows)
     auto wait_vmem = [&]() { __builtin_amdgcn_s_waitcnt(0x0F70); };
     if (NSTAGE == 2) {
-        if (st0 < st1) {
-            load_x(st0);
-            load_w(st0, lds);
-            wait_vmem();
-            store_x(st0, lds + W_UNITS);
-            store_w(st0, lds);
-        }
+        load_x(st0);
+        load_w(st0, lds);
+        wait_vmem();
+        store_x(st0, lds + W_UNITS);
+        store_w(st0, lds, lds + W_UNITS);
         __syncthreads();
-        for (int st = st0; st < st1; ++st) {
-            const int cur = (st - st0) & 1;
+        int cur = 0;
+        for (int st = st0; st + 1 < st1; ++st, cur ^= 1) {
             u32x4 *wl = lds + cur * stage_units, *xl = wl + W_UNITS;
             u32x4 *wn_ = lds + (cur ^ 1) * stage_units, *xn_ = wn_ + W_UNITS;
-            const bool more = st + 1 < st1;
-            if (more) {
-                load_x(st + 1);
-                load_w(st + 1, wn_);
-            }
-            // the loads get the whole step's MFMA time to arrive
-            compute(wl, xl, 0, T);
-            if (more) {
-                wait_vmem();
-                store_x(st + 1, xn_);
-                store_w(st + 1, wn_);
-            }
+            // region 1: the next step's loads are issued between the first half of the MFMAs
+            load_x(st + 1);
+            load_w(st + 1, wn_);
+            compute(wl, xl, 0, NIT_H);
+            interleave_hint<NIT_H * A * B, 1, 1, 2>();
+            wait_vmem();
+            // region 2: transposes, regroup and LDS stores between the second half
+            store_x(st + 1, xn_);
+            store_w(st + 1, wn_, xn_);
+            compute(wl, xl, NIT_H, NIT_ALL);
+            interleave_hint<(NIT_ALL - NIT_H) * A * B, 0, 2, 3>();
             __syncthreads();
         }
+        compute(lds + cur * stage_units, lds + cur * stage_units + W_UNITS, 0, NIT_ALL);
+        __syncthreads();                          // the buffers are reused by the epilogue
     } else {
         u32x4 *wl = lds, *xl = lds + W_UNITS;
-        if (st0 < st1) load_x(st0);
+        load_x(st0);
         for (int st = st0; st < st1; ++st) {
             __syncthreads();                      // everyone is done reading the buffers
             load_w(st, wl);
             wait_vmem();
             store_x(st, xl);
-            store_w(st, wl);
+            store_w(st, wl, xl);
             __syncthreads();
             if (st + 1 < st1) load_x(st + 1);
-            compute(wl, xl, 0, T);
+            compute(wl, xl, 0, NIT_ALL);
         }
+        __syncthreads();
     }
 
     // ---- epilogue: accumulator register e of lane (l32, lh) in block (i, j) is
@@ -442,7 +484,6 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void igemm_kernel(const Con
     // Bias, ReLU, one rounding to FP16; then each wave transposes its tile through LDS
     // (2-byte writes, 16-byte reads) so that a lane holds 8 consecutive pixels of one
     // output row and the global stores are 16, 8 or 4 bytes wide.
-    if (NSTAGE == 1) __syncthreads();            // the staging buffers are free from here on
     constexpr int EP = 40;                       // halves per LDS row: 32 pixels + pad (80 bytes)
     uint16_t *el = reinterpret_cast<uint16_t *>(lds) + wave * (32 * A * EP);
     float bv[A][16];
@@ -520,11 +561,8 @@ static hipError_t ensure_lds(Kern kern, size_t lds, std::atomic<size_t> &granted
 }
 
 template <int KS, int A, int B, int WM, int WN, int NPL, int XVEC, bool CALIGN, int NSTAGE, int MAXR>
-static hipError_t launch_igemm(const ConvArgs &a, hipStream_t stream)
+static hipError_t launch_igemm(const ConvArgs &a, size_t lds, hipStream_t stream)
 {
-    constexpr int W_UNITS = KS * KS * NPL * 32 * A * WM;
-    size_t lds = (size_t)NSTAGE * (W_UNITS + NPL * a.PH * a.PWU) * 16;
-    lds = lds < (size_t)WM * WN * 32 * A * 80 ? (size_t)WM * WN * 32 * A * 80 : lds;   // epilogue transpose
     const dim3 grid((unsigned)(((a.grid_blocks + 7) / 8) * 8)), block(64 * WM * WN);
     hipError_t e;
     if (a.split_k > 1) {
@@ -544,24 +582,30 @@ static hipError_t launch_igemm(const ConvArgs &a, hipStream_t stream)
 #define HGC_V1(KS, A, B, WM, WN, NPL, XVEC, CAL, NST, MAXR)                                     \
     {KS, A, B, WM, WN, NPL, XVEC, CAL, NST, MAXR,                                               \
      &launch_igemm<KS, A, B, WM, WN, NPL, XVEC, (CAL != 0), NST, MAXR>}
-// the four load forms of one tile shape: (vector|scalar input) x (vector|scalar weights)
-#define HGC_V4(KS, A, B, WM, WN, NPL, NST, MAXR, MAXR1)                                         \
-    HGC_V1(KS, A, B, WM, WN, NPL, 2, 1, NST, MAXR), HGC_V1(KS, A, B, WM, WN, NPL, 1, 1, NST, MAXR1),    \
-    HGC_V1(KS, A, B, WM, WN, NPL, 2, 0, NST, MAXR), HGC_V1(KS, A, B, WM, WN, NPL, 1, 0, NST, MAXR1)
+// aligned-channel forms of one tile shape for input loads of 8, 4, 2 and 1 pixels
+#define HGC_VX(KS, A, B, WM, WN, NPL, NST, R8, R4, R2, R1)                                      \
+    HGC_V1(KS, A, B, WM, WN, NPL, 8, 1, NST, R8), HGC_V1(KS, A, B, WM, WN, NPL, 4, 1, NST, R4), \
+    HGC_V1(KS, A, B, WM, WN, NPL, 2, 1, NST, R2), HGC_V1(KS, A, B, WM, WN, NPL, 1, 1, NST, R1)
+// ragged-channel forms (Cg % 8 != 0 or unaligned weights): 2- and 1-pixel input loads
+#define HGC_VR(KS, A, B, WM, WN, NPL, NST, R2, R1)                                              \
+    HGC_V1(KS, A, B, WM, WN, NPL, 2, 0, NST, R2), HGC_V1(KS, A, B, WM, WN, NPL, 1, 0, NST, R1)
 
 static const IgemmVariant g_variants[] = {
-    //     KS  A  B  WM WN NPL NST MAXR MAXR(scalar input)
-    HGC_V4(3, 2, 4, 2, 4, 2, 2, 2, 2),    // 128 ch x 512 px, 8 waves: throughput tile
-    HGC_V4(3, 2, 4, 2, 2, 2, 2, 2, 4),    // 128 ch x 256 px
-    HGC_V4(3, 2, 2, 1, 4, 2, 2, 2, 4),    //  64 ch x 256 px
-    HGC_V4(3, 2, 2, 1, 2, 4, 2, 2, 3),    //  64 ch x 128 px, 32 channels per step: latency tile
-    HGC_V4(3, 1, 2, 1, 2, 4, 2, 2, 4),    //  32 ch x 128 px
-    HGC_V4(1, 2, 4, 2, 2, 8, 2, 2, 4),    // pointwise 128 ch x 256 px, 64 channels per step
-    HGC_V4(1, 2, 2, 1, 4, 8, 2, 2, 4),    // pointwise  64 ch x 256 px
-    HGC_V4(1, 2, 2, 1, 2, 8, 2, 2, 4),    // pointwise  64 ch x 128 px
-    HGC_V4(5, 2, 2, 1, 4, 2, 1, 3, 4),    // 5x5  64 ch x 256 px
-    HGC_V1(7, 1, 2, 1, 4, 2, 2, 0, 1, 3),   // stem-like 7x7: 32 ch x 256 px
-    HGC_V1(7, 1, 2, 1, 4, 2, 1, 0, 1, 6),
+    //     KS  A  B  WM WN NPL NST  patch rounds in registers per input-load width
+    HGC_VX(3, 2, 4, 2, 4, 2, 2, 1, 1, 2, 2),    // 128 ch x 512 px, 8 waves: throughput tile
+    HGC_VX(3, 2, 4, 2, 2, 2, 2, 1, 2, 2, 4),    // 128 ch x 256 px
+    HGC_VX(3, 2, 2, 1, 4, 2, 2, 1, 1, 2, 4),    //  64 ch x 256 px
+    HGC_VR(3, 2, 2, 1, 4, 2, 2, 2, 4),
+    HGC_VX(3, 2, 2, 1, 2, 4, 2, 1, 2, 2, 3),    //  64 ch x 128 px, 32 channels per step: latency tile
+    HGC_VX(3, 1, 2, 1, 2, 4, 2, 1, 2, 2, 4),    //  32 ch x 128 px
+    HGC_VR(3, 1, 2, 1, 2, 4, 2, 2, 4),
+    HGC_VX(1, 2, 4, 2, 2, 8, 2, 1, 1, 2, 4),    // pointwise 128 ch x 256 px, 64 channels per step
+    HGC_VX(1, 2, 2, 1, 4, 8, 2, 1, 1, 2, 4),    // pointwise  64 ch x 256 px
+    HGC_VR(1, 2, 2, 1, 4, 8, 2, 2, 4),
+    HGC_VX(1, 2, 2, 1, 2, 8, 2, 1, 2, 2, 4),    // pointwise  64 ch x 128 px
+    HGC_VX(5, 2, 2, 1, 4, 2, 1, 1, 2, 3, 4),    // 5x5  64 ch x 256 px
+    HGC_VR(5, 2, 2, 1, 4, 2, 1, 3, 4),
+    HGC_VR(7, 1, 2, 1, 4, 2, 1, 3, 6),          // stem-like 7x7: 32 ch x 256 px
 };
 
 const IgemmVariant *igemm_variants(int *count)
