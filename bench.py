@@ -30,7 +30,9 @@ def main() -> int:
     ap.add_argument("--batch", type=int, default=1, help="images per layer call (headline: 1)")
     ap.add_argument("--config", default="vgg16", help="workload table (headline: vgg16)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
-    ap.add_argument("--no-ws", action="store_true", help="use the workspace-free entry point")
+    ap.add_argument("--entry", default="packed", choices=["packed", "ws", "plain"],
+                    help="C entry point: hgc_conv2d_forward_packed (weights re-laid out once, before "
+                         "timing, like a model load), hgc_conv2d_forward_ws or hgc_conv2d_forward")
     ap.add_argument("--per-layer", action="store_true", help="print a per-layer table to stderr")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -57,35 +59,42 @@ def main() -> int:
         host.append((x, w, b))
         xd, wd, bd = (torch.from_numpy(a).to(dev) for a in (x, w, b))
         y = torch.empty(L.y_shape, dtype=torch.float16, device=dev)
-        need = 0 if args.no_ws else hgc.conv2d_workspace_size(L)
+        need = 0 if args.entry == "plain" else hgc.conv2d_workspace_size(L)
         ws = torch.empty(max(need, 1), dtype=torch.uint8, device=dev)
-        bufs.append((hgc.ConvDesc.make(L), xd, wd, bd, y, ws, need))
+        wp = hgc.conv2d_pack_weights(L, wd)          # one-time re-layout, outside every timed region
+        bufs.append((hgc.ConvDesc.make(L), xd, wd, bd, y, ws, need, wp))
     stream = torch.cuda.current_stream(dev)
     sh = stream.cuda_stream
 
-    def launch(i):
-        d, xd, wd, bd, y, ws, need = bufs[i]
-        if args.no_ws:
+    def launch(i, entry=args.entry):
+        d, xd, wd, bd, y, ws, need, wp = bufs[i]
+        if entry == "plain":
             st = hgc.forward_raw(d, xd.data_ptr(), wd.data_ptr(), bd.data_ptr(), y.data_ptr(), sh)
-        else:
+        elif entry == "ws":
             st = hgc.forward_ws_raw(d, xd.data_ptr(), wd.data_ptr(), bd.data_ptr(), y.data_ptr(),
                                     ws.data_ptr(), need, sh)
+        else:
+            st = hgc.forward_packed_raw(d, xd.data_ptr(), wp.data_ptr(), bd.data_ptr(), y.data_ptr(),
+                                        ws.data_ptr(), need, sh)
         if st != 0:
             raise hgc.HgcError(st, layers[i].name)
 
-    def step():
-        for i in range(len(layers)):
-            launch(i)
+    def timed(entry, steps, warmup):
+        for _ in range(warmup):
+            for i in range(len(layers)):
+                launch(i, entry)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            for i in range(len(layers)):
+                launch(i, entry)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / steps
 
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step()
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    ms_per_step = timed(args.entry, args.steps, args.warmup)
+    # the same stack through the entry point that takes the caller's weight layout
+    other = "ws" if args.entry == "packed" else None
+    ms_other = timed(other, max(1, args.steps // 4), max(1, args.warmup // 4)) if other else None
     flops_step = sum(L.flops for L in layers)
     bytes_step = sum(L.bytes for L in layers)
     tflops = flops_step / (ms_per_step * 1e-3) / 1e12
@@ -103,7 +112,7 @@ def main() -> int:
         e1.record(stream)
         e1.synchronize()
         us = e0.elapsed_time(e1) * 1e3 / reps
-        plan = hgc.conv2d_plan(L, not args.no_ws).as_dict()
+        plan = hgc.conv2d_plan(L, args.entry != "plain", args.entry == "packed").as_dict()
         per_layer.append({
             "layer": L.name, "path": plan["path_name"], "variant": plan["variant"],
             "tile": [plan["tile_m"], plan["tile_h"], plan["tile_w"]], "split_k": plan["split_k"],
@@ -163,7 +172,11 @@ def main() -> int:
         "dtype": "f16 (fp32 accumulate)", "data": "synthetic",
         "config": {"workload": "%s conv stack, N=%d, 3x3 s1 p1, bias+ReLU, %d layers, %.2f GFLOP, %.1f MB" % (
             args.config, args.batch, len(layers), flops_step / 1e9, bytes_step / 1e6),
-            "entry": "hgc_conv2d_forward" if args.no_ws else "hgc_conv2d_forward_ws"},
+            "entry": {"packed": "hgc_conv2d_forward_packed (weights packed once before timing)",
+                      "ws": "hgc_conv2d_forward_ws", "plain": "hgc_conv2d_forward"}[args.entry]},
+        "caller_layout_weights": None if ms_other is None else {
+            "entry": "hgc_conv2d_forward_ws", "ms_per_step": ms_other,
+            "value": flops_step / (ms_other * 1e-3) / 1e12, "unit": "TFLOP/s"},
         "roofline": roof,
         "cpu_baseline": cpu,
     }

@@ -62,6 +62,7 @@ typedef int32_t hgc_status;
 #define HGC_ERR_TOO_LARGE  (-3)  /* a tensor has more than 2^31 - 1 elements            */
 #define HGC_ERR_WORKSPACE  (-4)  /* workspace NULL or smaller than required             */
 #define HGC_ERR_LAUNCH     (-5)  /* the HIP runtime refused a launch                    */
+#define HGC_ERR_ALIGNMENT  (-6)  /* a packed weight buffer is not 256-byte aligned      */
 
 /* Algorithms (hgc_plan.path). */
 #define HGC_PATH_AUTO       0    /* only as an argument of hgc_set_forced_path          */
@@ -115,9 +116,31 @@ hgc_status hgc_conv2d_workspace_size(const hgc_conv2d_desc *desc, size_t *bytes_
 
 /*
  * The algorithm and launch shape a call would use.  with_workspace = 0 describes
- * hgc_conv2d_forward, 1 describes hgc_conv2d_forward_ws.  Host-only.
+ * hgc_conv2d_forward, 1 hgc_conv2d_forward_ws, 3 hgc_conv2d_forward_packed.  Host-only.
  */
 hgc_status hgc_conv2d_plan(const hgc_conv2d_desc *desc, int32_t with_workspace, hgc_plan *plan_out);
+
+/*
+ * One-time weight re-layout.  The engine the paper describes converts weights once,
+ * offline, so that no conversion work is left on the inference path (Section 3.3:
+ * FP16 weight files and the model converter); hgc_conv2d_pack_weights applies the
+ * same rule to the weight LAYOUT: it copies w into a device buffer that holds the
+ * weights verbatim plus a copy ordered the way the MFMA kernels consume them
+ * (16-byte units [group][8-row block][8-channel plane][tap][row] of 8 channels, zero
+ * filled past num_output/group and C/group).  Pure data movement, bit-exact.
+ *
+ * hgc_conv2d_packed_weights_size: bytes of that buffer for a descriptor (host-only).
+ * hgc_conv2d_pack_weights: enqueue the re-layout of w (device, caller's layout)
+ *   into w_packed (device, 256-byte aligned, caller-owned, at least the size above).
+ * hgc_conv2d_forward_packed: hgc_conv2d_forward_ws with w_packed in place of w; the
+ *   descriptor must be the one the buffer was packed for.  Same results up to the
+ *   stated tolerance, same error order; additionally HGC_ERR_ALIGNMENT.
+ */
+hgc_status hgc_conv2d_packed_weights_size(const hgc_conv2d_desc *desc, size_t *bytes_out);
+hgc_status hgc_conv2d_pack_weights(const hgc_conv2d_desc *desc, const void *w, void *w_packed, void *stream);
+hgc_status hgc_conv2d_forward_packed(const hgc_conv2d_desc *desc, const void *x, const void *w_packed,
+                                     const void *b, void *y, void *workspace, size_t workspace_bytes,
+                                     void *stream);
 
 /*
  * Test/diagnostic control: force one algorithm (HGC_PATH_*) for every later call
@@ -127,6 +150,14 @@ hgc_status hgc_conv2d_plan(const hgc_conv2d_desc *desc, int32_t with_workspace, 
  * Returns the previous forced path.
  */
 int32_t hgc_set_forced_path(int32_t path, int32_t tile_variant);
+
+/*
+ * Test/diagnostic control for the implicit-GEMM path: force the output window
+ * width (tile_w = 2^log2_tile_w) and the number of reduction slices; -1 = automatic.
+ * Combinations that do not fit are ignored (the planner then finds no candidate
+ * and the call falls back to HGC_PATH_DIRECT).
+ */
+void hgc_set_forced_tiling(int32_t log2_tile_w, int32_t split_k);
 
 /* Static, NUL-terminated description of a status code. */
 const char *hgc_status_string(hgc_status status);

@@ -86,6 +86,14 @@ def load():
     lib.hgc_conv2d_plan.restype = ctypes.c_int32
     lib.hgc_set_forced_path.argtypes = [ctypes.c_int32, ctypes.c_int32]
     lib.hgc_set_forced_path.restype = ctypes.c_int32
+    lib.hgc_conv2d_packed_weights_size.argtypes = [dp, ctypes.POINTER(ctypes.c_size_t)]
+    lib.hgc_conv2d_packed_weights_size.restype = ctypes.c_int32
+    lib.hgc_conv2d_pack_weights.argtypes = [dp, vp, vp, vp]
+    lib.hgc_conv2d_pack_weights.restype = ctypes.c_int32
+    lib.hgc_conv2d_forward_packed.argtypes = [dp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
+    lib.hgc_conv2d_forward_packed.restype = ctypes.c_int32
+    lib.hgc_set_forced_tiling.argtypes = [ctypes.c_int32, ctypes.c_int32]
+    lib.hgc_set_forced_tiling.restype = None
     lib.hgc_status_string.argtypes = [ctypes.c_int32]
     lib.hgc_status_string.restype = ctypes.c_char_p
     lib.hgc_version.restype = ctypes.c_int32
@@ -106,6 +114,10 @@ def set_forced_path(path: int = PATH_AUTO, tile_variant: int = -1) -> int:
     return int(load().hgc_set_forced_path(int(path), int(tile_variant)))
 
 
+def set_forced_tiling(log2_tile_w: int = -1, split_k: int = -1) -> None:
+    load().hgc_set_forced_tiling(int(log2_tile_w), int(split_k))
+
+
 def conv2d_workspace_size(desc) -> int:
     d = ConvDesc.make(desc)
     n = ctypes.c_size_t(0)
@@ -115,10 +127,11 @@ def conv2d_workspace_size(desc) -> int:
     return int(n.value)
 
 
-def conv2d_plan(desc, with_workspace: bool = False) -> Plan:
+def conv2d_plan(desc, with_workspace: bool = False, packed: bool = False) -> Plan:
     d = ConvDesc.make(desc)
     p = Plan()
-    st = load().hgc_conv2d_plan(ctypes.byref(d), 1 if with_workspace else 0, ctypes.byref(p))
+    mode = 3 if packed else (1 if with_workspace else 0)
+    st = load().hgc_conv2d_plan(ctypes.byref(d), mode, ctypes.byref(p))
     if st != 0:
         raise HgcError(st, "hgc_conv2d_plan")
     return p
@@ -183,4 +196,61 @@ def conv2d_forward_ws(desc, x, w, b=None, y=None, workspace=None):
                         y.data_ptr(), ws_ptr, ws_bytes, stream)
     if st != 0:
         raise HgcError(st, "hgc_conv2d_forward_ws")
+    return y
+
+
+def conv2d_packed_weights_size(desc) -> int:
+    d = ConvDesc.make(desc)
+    n = ctypes.c_size_t(0)
+    st = load().hgc_conv2d_packed_weights_size(ctypes.byref(d), ctypes.byref(n))
+    if st != 0:
+        raise HgcError(st, "hgc_conv2d_packed_weights_size")
+    return int(n.value)
+
+
+def conv2d_pack_weights(desc, w, w_packed=None):
+    """hgc_conv2d_pack_weights on torch tensors; returns the packed uint8 CUDA tensor."""
+    import torch
+    d = ConvDesc.make(desc)
+    _check_tensor(w, "w")
+    need = conv2d_packed_weights_size(d)
+    if w_packed is None:
+        w_packed = torch.empty(need, dtype=torch.uint8, device=w.device)
+    if w_packed.numel() * w_packed.element_size() < need:
+        raise ValueError("w_packed is too small")
+    stream = torch.cuda.current_stream(w.device).cuda_stream
+    st = int(load().hgc_conv2d_pack_weights(ctypes.byref(d), w.data_ptr(), w_packed.data_ptr(), stream or None))
+    if st != 0:
+        raise HgcError(st, "hgc_conv2d_pack_weights")
+    return w_packed
+
+
+def forward_packed_raw(desc: Optional[ConvDesc], x: int, wp: int, b: int, y: int, ws: int, ws_bytes: int,
+                       stream: int = 0) -> int:
+    dref = ctypes.byref(desc) if desc is not None else None
+    return int(load().hgc_conv2d_forward_packed(dref, x or None, wp or None, b or None, y or None,
+                                                ws or None, int(ws_bytes), stream or None))
+
+
+def conv2d_forward_packed(desc, x, w_packed, b=None, y=None, workspace=None):
+    """hgc_conv2d_forward_packed; w_packed comes from conv2d_pack_weights."""
+    import torch
+    d = ConvDesc.make(desc)
+    _check_tensor(x, "x", (d.N, d.C, d.H, d.W))
+    if d.bias:
+        if b is None:
+            raise ValueError("bias=1 needs b")
+        _check_tensor(b, "b", (d.num_output,))
+    if y is None:
+        y = torch.empty(d.out_shape(), dtype=torch.float16, device=x.device)
+    else:
+        _check_tensor(y, "y", d.out_shape())
+    ws_ptr, ws_bytes = 0, 0
+    if workspace is not None:
+        ws_ptr, ws_bytes = workspace.data_ptr(), workspace.numel() * workspace.element_size()
+    stream = torch.cuda.current_stream(x.device).cuda_stream
+    st = forward_packed_raw(d, x.data_ptr(), w_packed.data_ptr(), b.data_ptr() if (d.bias and b is not None) else 0,
+                            y.data_ptr(), ws_ptr, ws_bytes, stream)
+    if st != 0:
+        raise HgcError(st, "hgc_conv2d_forward_packed")
     return y

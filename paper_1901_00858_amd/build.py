@@ -9,8 +9,9 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libhgc.so")
-SOURCES = ["api.hip", "igemm.hip", "direct.hip"]
-HEADERS = [os.path.join(CSRC, "hgc_internal.h"), os.path.join(ROOT, "include", "hgc.h")]
+SOURCES = ["api.hip", "igemm_raw.hip", "igemm_packed.hip", "direct.hip", "pack.hip"]
+HEADERS = [os.path.join(CSRC, "hgc_internal.h"), os.path.join(CSRC, "igemm_kernel.h"),
+           os.path.join(ROOT, "include", "hgc.h")]
 
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",

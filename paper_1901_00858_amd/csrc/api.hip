@@ -16,6 +16,8 @@ namespace hgc {
 static std::atomic<int> g_forced_path{HGC_PATH_AUTO};
 static std::atomic<int> g_forced_variant{-1};
 static thread_local int g_last_hip_error = 0;
+static std::atomic<int> g_forced_log2_tw{-1};
+static std::atomic<int> g_forced_split{-1};
 
 static constexpr long long kMaxLds = 160 * 1024;
 
@@ -106,15 +108,16 @@ static double estimate_cycles(const Geometry &g, const Candidate &c)
     return total;
 }
 
-static bool plan_igemm(const Geometry &g, bool with_ws, int x_align, bool w_al16, int forced_variant,
-                       bool force_split, Plan *pl)
+static bool plan_igemm(const Geometry &g, bool with_ws, int x_align, bool w_al16, bool packed,
+                       int forced_variant, bool force_split, Plan *pl)
 {
     int nv = 0;
-    const IgemmVariant *vs = igemm_variants(&nv);
+    const IgemmVariant *vs = packed ? igemm_variants_packed(&nv) : igemm_variants_raw(&nv);
     // widest input load: W and x's byte alignment / 2 must be multiples of the pixel count
     int want_xvec = 8;
     while (want_xvec > 1 && (g.W % want_xvec || x_align % (2 * want_xvec))) want_xvec >>= 1;
-    const int want_cal = (g.Cg % 8 == 0 && w_al16) ? 1 : 0;
+    // packed weights are always 16-byte units; only the input's channel predicates care about Cg % 8
+    const int want_cal = (g.Cg % 8 == 0 && (w_al16 || packed)) ? 1 : 0;
     Candidate best;
     best.v = nullptr;
     best.cycles = 1e300;
@@ -130,7 +133,10 @@ static bool plan_igemm(const Geometry &g, bool with_ws, int x_align, bool w_al16
             if (v.xvec != xv || v.calign != want_cal) continue;
         }
         const int BN = v.BN();
+        const int f_tw = g_forced_log2_tw.load(std::memory_order_relaxed);
+        const int f_sp = g_forced_split.load(std::memory_order_relaxed);
         for (int j = 2; (1 << j) <= BN && j <= 6; ++j) {
+            if (f_tw >= 0 && j != f_tw) continue;
             Candidate c;
             c.v = &v;
             c.log2_tw = j;
@@ -148,8 +154,10 @@ static bool plan_igemm(const Geometry &g, bool with_ws, int x_align, bool w_al16
             c.grid = (long long)c.tiles_m * c.tiles_w * c.tiles_h * g.G * g.N;
             if (c.grid > (1 << 30)) continue;
             const int max_split = (with_ws && c.nsteps >= 2) ? std::min(c.nsteps, 32) : 1;
-            for (int sp = 1; sp <= max_split; sp = (sp < 4 ? sp + 1 : sp * 2)) {
+            for (int sp = 1; sp <= max_split; ++sp) {
+                if (sp > 4 && (sp & (sp - 1)) && sp != max_split) continue;   // 1..4, powers of two, and the maximum
                 if (force_split && sp < 2 && max_split >= 2) continue;
+                if (f_sp >= 1 && sp != std::min(f_sp, max_split)) continue;
                 c.steps_per_split = ceil_div(c.nsteps, sp);
                 c.split = ceil_div(c.nsteps, c.steps_per_split);
                 if (c.grid * c.split > (1 << 30)) continue;
@@ -179,7 +187,7 @@ static bool plan_igemm(const Geometry &g, bool with_ws, int x_align, bool w_al16
     return true;
 }
 
-static void make_plan(const Geometry &g, bool with_ws, int x_align, bool w_al16, Plan *pl)
+static void make_plan(const Geometry &g, bool with_ws, int x_align, bool w_al16, bool packed, Plan *pl)
 {
     std::memset(pl, 0, sizeof(*pl));
     base_args(g, &pl->args);
@@ -203,7 +211,7 @@ static void make_plan(const Geometry &g, bool with_ws, int x_align, bool w_al16,
     }
     if (path == HGC_PATH_IGEMM || path == HGC_PATH_IGEMM_SPLITK) {
         const bool ws = with_ws && (forced != HGC_PATH_IGEMM);
-        if (plan_igemm(g, ws, x_align, w_al16, fvar, forced == HGC_PATH_IGEMM_SPLITK && with_ws, pl))
+        if (plan_igemm(g, ws, x_align, w_al16, packed, fvar, forced == HGC_PATH_IGEMM_SPLITK && with_ws, pl))
             return;
         base_args(g, &pl->args);
     }
@@ -213,7 +221,7 @@ static void make_plan(const Geometry &g, bool with_ws, int x_align, bool w_al16,
 }
 
 static hgc_status run(const hgc_conv2d_desc *desc, const void *x, const void *w, const void *b,
-                      void *y, void *ws, size_t ws_bytes, bool with_ws, void *stream)
+                      void *y, void *ws, size_t ws_bytes, bool with_ws, bool packed, void *stream)
 {
     if (!desc || !x || !w || !y) return HGC_ERR_NULL;
     if (desc->bias == 1 && !b) return HGC_ERR_NULL;
@@ -224,7 +232,8 @@ static hgc_status run(const hgc_conv2d_desc *desc, const void *x, const void *w,
     int x_align = 16;                            // byte alignment of x, capped at 16
     while (x_align > 2 && ((uintptr_t)x % x_align)) x_align >>= 1;
     const bool w_al16 = ((uintptr_t)w & 15) == 0;
-    make_plan(g, with_ws, x_align, w_al16, &pl);
+    if (packed && ((uintptr_t)w & 255)) return HGC_ERR_ALIGNMENT;
+    make_plan(g, with_ws, x_align, w_al16, packed, &pl);
     if (pl.pub.workspace_bytes > 0) {
         // the size reported to the caller assumed aligned tensors; an unaligned call
         // may need the same or less, never more (same tiles, same split rule)
@@ -238,6 +247,14 @@ static hgc_status run(const hgc_conv2d_desc *desc, const void *x, const void *w,
     a.ws = static_cast<float *>(ws);
     a.x_bytes = (uint32_t)(2LL * g.N * g.C * g.H * g.W);
     a.w_bytes = (uint32_t)(2LL * g.M * g.Kg);
+    if (packed) {
+        const PackedLayout lay = packed_layout(g);
+        a.w_bytes = (uint32_t)lay.total;
+        a.wp_off = (uint32_t)lay.igemm_off;
+        a.wp_zero = (uint32_t)lay.zero_off;
+        a.MB8 = lay.MB8;
+        a.NP8 = lay.NP8;
+    }
     {   // widest output store: divides Wo and the window width, and y's byte alignment allows it
         int ov = 8;
         while (ov > 1 && (g.Wo % ov || (1 << a.log2_tw) % ov || ((uintptr_t)y % (2 * ov)))) ov >>= 1;
@@ -271,14 +288,14 @@ extern "C" {
 hgc_status hgc_conv2d_forward(const hgc_conv2d_desc *desc, const void *x, const void *w,
                               const void *b, void *y, void *stream)
 {
-    return run(desc, x, w, b, y, nullptr, 0, false, stream);
+    return run(desc, x, w, b, y, nullptr, 0, false, false, stream);
 }
 
 hgc_status hgc_conv2d_forward_ws(const hgc_conv2d_desc *desc, const void *x, const void *w,
                                  const void *b, void *y, void *workspace, size_t workspace_bytes,
                                  void *stream)
 {
-    return run(desc, x, w, b, y, workspace, workspace_bytes, true, stream);
+    return run(desc, x, w, b, y, workspace, workspace_bytes, true, false, stream);
 }
 
 hgc_status hgc_conv2d_workspace_size(const hgc_conv2d_desc *desc, size_t *bytes_out)
@@ -288,13 +305,15 @@ hgc_status hgc_conv2d_workspace_size(const hgc_conv2d_desc *desc, size_t *bytes_
     hgc_status st = validate(desc, &g);
     if (st != HGC_OK) return st;
     Plan pl;
-    make_plan(g, true, 16, true, &pl);
+    make_plan(g, true, 16, true, false, &pl);
     long long need = pl.pub.workspace_bytes;
     // a less aligned tensor base selects a different instantiation with its own tiles
     for (int xa = 2; xa <= 16; xa *= 2)
         for (int wa = 0; wa < 2; ++wa) {
             Plan alt;
-            make_plan(g, true, xa, wa != 0, &alt);
+            make_plan(g, true, xa, wa != 0, false, &alt);
+            if (alt.pub.workspace_bytes > need) need = alt.pub.workspace_bytes;
+            make_plan(g, true, xa, wa != 0, true, &alt);
             if (alt.pub.workspace_bytes > need) need = alt.pub.workspace_bytes;
         }
     *bytes_out = (size_t)need;
@@ -308,7 +327,7 @@ hgc_status hgc_conv2d_plan(const hgc_conv2d_desc *desc, int32_t with_workspace, 
     hgc_status st = validate(desc, &g);
     if (st != HGC_OK) return st;
     Plan pl;
-    make_plan(g, with_workspace != 0, 16, true, &pl);
+    make_plan(g, (with_workspace & 1) != 0, 16, true, (with_workspace & 2) != 0, &pl);
     *plan_out = pl.pub;
     return HGC_OK;
 }
@@ -320,6 +339,50 @@ int32_t hgc_set_forced_path(int32_t path, int32_t tile_variant)
     return g_forced_path.exchange(path, std::memory_order_relaxed);
 }
 
+hgc_status hgc_conv2d_packed_weights_size(const hgc_conv2d_desc *desc, size_t *bytes_out)
+{
+    if (!desc || !bytes_out) return HGC_ERR_NULL;
+    Geometry g;
+    hgc_status st = validate(desc, &g);
+    if (st != HGC_OK) return st;
+    const PackedLayout lay = packed_layout(g);
+    if (lay.total > 0xFFFFFFF0LL) return HGC_ERR_TOO_LARGE;
+    *bytes_out = (size_t)lay.total;
+    return HGC_OK;
+}
+
+hgc_status hgc_conv2d_pack_weights(const hgc_conv2d_desc *desc, const void *w, void *w_packed, void *stream)
+{
+    if (!desc || !w || !w_packed) return HGC_ERR_NULL;
+    Geometry g;
+    hgc_status st = validate(desc, &g);
+    if (st != HGC_OK) return st;
+    const PackedLayout lay = packed_layout(g);
+    if (lay.total > 0xFFFFFFF0LL) return HGC_ERR_TOO_LARGE;
+    if ((uintptr_t)w_packed & 255) return HGC_ERR_ALIGNMENT;
+    const hipError_t e = launch_pack_weights(g, lay, static_cast<const uint16_t *>(w),
+                                             static_cast<uint8_t *>(w_packed), static_cast<hipStream_t>(stream));
+    g_last_hip_error = (int)e;
+    return e == hipSuccess ? HGC_OK : HGC_ERR_LAUNCH;
+}
+
+hgc_status hgc_conv2d_forward_packed(const hgc_conv2d_desc *desc, const void *x, const void *w_packed,
+                                     const void *b, void *y, void *workspace, size_t workspace_bytes,
+                                     void *stream)
+{
+    if (desc && w_packed) {
+        Geometry g;
+        if (validate(desc, &g) == HGC_OK && packed_layout(g).total > 0xFFFFFFF0LL) return HGC_ERR_TOO_LARGE;
+    }
+    return run(desc, x, w_packed, b, y, workspace, workspace_bytes, true, true, stream);
+}
+
+void hgc_set_forced_tiling(int32_t log2_tile_w, int32_t split_k)
+{
+    g_forced_log2_tw.store(log2_tile_w, std::memory_order_relaxed);
+    g_forced_split.store(split_k, std::memory_order_relaxed);
+}
+
 const char *hgc_status_string(hgc_status status)
 {
     switch (status) {
@@ -329,6 +392,7 @@ const char *hgc_status_string(hgc_status status)
     case HGC_ERR_TOO_LARGE: return "a tensor has more than 2^31-1 elements";
     case HGC_ERR_WORKSPACE: return "workspace missing or too small";
     case HGC_ERR_LAUNCH: return "HIP launch failed";
+    case HGC_ERR_ALIGNMENT: return "packed weight buffer is not 256-byte aligned";
     default: return "unknown status";
     }
 }

@@ -34,8 +34,11 @@ struct ConvArgs {
     int tiles_w, tiles_h, tiles_m;
     int PH, PWU;         // input halo patch: rows, and 16-byte units (pixels) per row
     int nsteps;          // channel blocks of CB channels per group: ceil(Cg / CB)
-    uint32_t x_bytes;    // size of x and w in bytes (buffer-load range checks)
+    uint32_t x_bytes;    // size of x and w (or the packed weight buffer) in bytes (buffer-load range checks)
     uint32_t w_bytes;
+    uint32_t wp_off;     // packed weights: byte offset of the implicit-GEMM layout, and of the zero page
+    uint32_t wp_zero;
+    int MB8, NP8;        // packed weights: 8-row blocks per group, 8-channel planes per group
     int out_vec;         // output pixels per store (8, 4, 2 or 1): divides Wo and tile_w, fits y's alignment
     int grid_blocks;     // workgroups that have work (the launch pads to a multiple of 8)
     int split_k;         // reduction slices (1 = none)
@@ -62,6 +65,7 @@ struct IgemmVariant {
     int npl;             // 8-channel planes per K step (CB = 8 * npl)
     int xvec;            // pixels per global load of the input (1 or 2)
     int calign;          // 1: Cg % 8 == 0, weights fetched as 16-byte vectors
+    int packed;          // 1: weights in the pre-packed layout
     int nstage;          // LDS buffers (2 = double buffered)
     int max_rounds;      // patch staging rounds pipelined through registers
     hipError_t (*launch)(const ConvArgs &, size_t lds_bytes, hipStream_t stream);
@@ -77,7 +81,20 @@ struct IgemmVariant {
     }
 };
 
-const IgemmVariant *igemm_variants(int *count);
+const IgemmVariant *igemm_variants_raw(int *count);
+const IgemmVariant *igemm_variants_packed(int *count);
+
+// Layout of a packed weight buffer (all offsets in bytes, multiples of 256):
+// [0, raw) the caller's weights verbatim, [igemm_off, zero_off) 16-byte units
+// [G][ceil(Mg/8)][ceil(Cg/8)][k*k][8 rows] of 8 channels, zero filled past Mg and Cg,
+// [zero_off, total) a page of zeros.
+struct PackedLayout {
+    long long raw_bytes, igemm_off, zero_off, total;
+    int MB8, NP8;
+};
+PackedLayout packed_layout(const Geometry &g);
+hipError_t launch_pack_weights(const Geometry &g, const PackedLayout &pl, const uint16_t *w, uint8_t *packed,
+                               hipStream_t stream);
 
 hipError_t launch_direct(const ConvArgs &a, hipStream_t stream);
 hipError_t launch_depthwise(const ConvArgs &a, hipStream_t stream);

@@ -1,4 +1,7 @@
-// Implicit-GEMM convolution forward on FP16 MFMA for gfx950.
+// Implicit-GEMM convolution forward on FP16 MFMA for gfx950: the kernel template and
+// its instantiation table.  Included by igemm_raw.hip and igemm_packed.hip, which set
+// HGC_IGEMM_PACKED (0: weights in the caller's layout, 1: pre-packed weights) and
+// HGC_IGEMM_ACCESSOR (the name of the function that returns the table).
 //
 // Per group the layer is the contraction  Y[Mg x P] = W[Mg x Kg] * B[Kg x P],
 // where B is the im2col matrix of the input (Caffe's formulation, which the paper
@@ -33,6 +36,7 @@
 // execute in order, so no barrier is needed inside the wave.
 // With NSTAGE = 2 the LDS buffers are double: the loads of step s+1 are issued
 // before the MFMAs of step s and are stored to the other buffer after them.
+#pragma once
 #include <atomic>
 
 #include "hgc_internal.h"
@@ -153,11 +157,12 @@ __device__ __forceinline__ void interleave_hint()
 // KS: kernel extent.  A, B: 32x32 accumulator blocks per wave along channels and
 // pixels.  WAVES_M x WAVES_N waves per workgroup.  NPL: 8-channel planes per K
 // step.  XVEC: input pixels per global load (1, 2, 4 or 8; W and the byte alignment
-// of x must be multiples of it).  CALIGN: Cg % 8 == 0 and a 16-byte aligned weight base.  NSTAGE: LDS
-// buffers (1 or 2).  MAXR: patch staging rounds held in registers.  SPLITK: write
+// of x must be multiples of it).  CALIGN: Cg % 8 == 0 and a 16-byte aligned weight base.
+// PACKED: weights come from the pre-packed layout (see pack.hip) and need no regrouping.
+// NSTAGE: LDS buffers (1 or 2).  MAXR: patch staging rounds held in registers.  SPLITK: write
 // FP32 partial sums of a slice of the channel blocks instead of the output.
-template <int KS, int A, int B, int WAVES_M, int WAVES_N, int NPL, int XVEC, bool CALIGN, int NSTAGE,
-          int MAXR, bool SPLITK>
+template <int KS, int A, int B, int WAVES_M, int WAVES_N, int NPL, int XVEC, bool CALIGN, bool PACKED,
+          int NSTAGE, int MAXR, bool SPLITK>
 __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void igemm_kernel(const ConvArgs p)
 {
     constexpr int NW = WAVES_M * WAVES_N;
@@ -222,7 +227,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void igemm_kernel(const Con
     const int Cg = p.Cg, Mg = p.Mg;
 
     const __amdgpu_buffer_rsrc_t rx = make_rsrc(p.x, p.x_bytes);
-    const __amdgpu_buffer_rsrc_t rw = make_rsrc(p.w, p.w_bytes);
+    const __amdgpu_buffer_rsrc_t rw = make_rsrc(p.w, p.w_bytes);   // raw weights, or the whole packed buffer
 
     // ---- staging maps (do not depend on the K step) ----
     const int ipr = PWU / XVEC;                  // items per patch row
@@ -261,9 +266,23 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void igemm_kernel(const Con
 
     // ---- weights ----
     const uint32_t wgrp_off = 2u * (uint32_t)(g * Mg * Cg * T);           // M*Kg < 2^31: fits
-    uint32_t wvoff[CALIGN ? WLR : 1];            // byte offset of (row, chunk) at K step 0
-    int wpl8[CALIGN ? WLR : 1];
-    if (CALIGN) {
+    constexpr bool WDMA = CALIGN || PACKED;      // weights arrive by LDS-direct loads
+    uint32_t wvoff[WDMA ? WLR : 1];              // byte offset of this lane's chunk at K step 0
+    int wpl8[WDMA ? WLR : 1];
+    if (PACKED) {
+        // packed layout: units [G][Mg/8][Cg/8][T][8 rows] of 8 channels; unit u of the
+        // slice is (tap, plane, row) in the order the MFMA operand reads want
+#pragma unroll
+        for (int k = 0; k < WLR; ++k) {
+            const int u = lane + 64 * k;
+            const int t = u / (NPL * RPW), pl = (u / RPW) % NPL, r = u % RPW;
+            const int m = m0 + wave * RPW + r;
+            const bool ok = (u < WCH) && (m < p.MB8 * 8);
+            wvoff[k] = ok ? p.wp_off + 16u * (uint32_t)((((g * p.MB8 + (m >> 3)) * p.NP8 + pl) * T + t) * 8 + (m & 7))
+                          : p.wp_zero;
+            wpl8[k] = pl;
+        }
+    } else if (CALIGN) {
 #pragma unroll
         for (int k = 0; k < WLR; ++k) {
             const int id = lane + 64 * k;
@@ -274,18 +293,30 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void igemm_kernel(const Con
         }
     }
     auto load_w = [&](int st, u32x4 *wl) {
-        if (!CALIGN) return;
+        if (!WDMA) return;
         u32x4 *mine = wl + wave * WSL;
-        const uint32_t soff = 2u * (uint32_t)(st * CB * T);
+        if (PACKED) {
+            const uint32_t soff = 16u * (uint32_t)(st * NPL * T * 8);
 #pragma unroll
-        for (int k = 0; k < WLR; ++k) {
-            const uint32_t vo = (st * CB + wpl8[k] < Cg) ? wvoff[k] : kNoLoad;
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(rw, (lds_ptr_t)(mine + 64 * k), 16, vo, soff, 0, 0);
+            for (int k = 0; k < WLR; ++k) {
+                // planes past the last channel: read the zero page (the scalar offset must not move it)
+                const bool inside = (wvoff[k] != p.wp_zero) && (st * NPL + wpl8[k] < p.NP8);
+                const uint32_t vo = inside ? wvoff[k] : p.wp_zero - soff;
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rw, (lds_ptr_t)(mine + 64 * k), 16, vo, soff, 0, 0);
+            }
+        } else {
+            const uint32_t soff = 2u * (uint32_t)(st * CB * T);
+#pragma unroll
+            for (int k = 0; k < WLR; ++k) {
+                const uint32_t vo = (st * CB + wpl8[k] < Cg) ? wvoff[k] : kNoLoad;
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rw, (lds_ptr_t)(mine + 64 * k), 16, vo, soff, 0, 0);
+            }
         }
     };
     // regroup items: lanes past the item count redo item (lane % WIT) and write the dump unit
     auto store_w = [&](int st, u32x4 *wl, u32x4 *xl) {
         u32x4 *mine = wl + wave * WSL;           // this wave's slice: final layout [T][NPL][RPW]
+        if (PACKED) return;                      // already in the final layout
         if (CALIGN) {
             // the raw rows ([row][CPR] chunks) have landed (caller waited on vmcnt);
             // read back one (row, plane) per lane: halves e = c*T + tap, c = 0..7 ...
@@ -560,19 +591,19 @@ static hipError_t ensure_lds(Kern kern, size_t lds, std::atomic<size_t> &granted
     return e;
 }
 
-template <int KS, int A, int B, int WM, int WN, int NPL, int XVEC, bool CALIGN, int NSTAGE, int MAXR>
+template <int KS, int A, int B, int WM, int WN, int NPL, int XVEC, bool CALIGN, bool PACKED, int NSTAGE, int MAXR>
 static hipError_t launch_igemm(const ConvArgs &a, size_t lds, hipStream_t stream)
 {
     const dim3 grid((unsigned)(((a.grid_blocks + 7) / 8) * 8)), block(64 * WM * WN);
     hipError_t e;
     if (a.split_k > 1) {
         static std::atomic<size_t> granted{0};
-        auto kern = igemm_kernel<KS, A, B, WM, WN, NPL, XVEC, CALIGN, NSTAGE, MAXR, true>;
+        auto kern = igemm_kernel<KS, A, B, WM, WN, NPL, XVEC, CALIGN, PACKED, NSTAGE, MAXR, true>;
         if ((e = ensure_lds(kern, lds, granted)) != hipSuccess) return e;
         hipLaunchKernelGGL(kern, grid, block, lds, stream, a);
     } else {
         static std::atomic<size_t> granted{0};
-        auto kern = igemm_kernel<KS, A, B, WM, WN, NPL, XVEC, CALIGN, NSTAGE, MAXR, false>;
+        auto kern = igemm_kernel<KS, A, B, WM, WN, NPL, XVEC, CALIGN, PACKED, NSTAGE, MAXR, false>;
         if ((e = ensure_lds(kern, lds, granted)) != hipSuccess) return e;
         hipLaunchKernelGGL(kern, grid, block, lds, stream, a);
     }
@@ -580,8 +611,8 @@ static hipError_t launch_igemm(const ConvArgs &a, size_t lds, hipStream_t stream
 }
 
 #define HGC_V1(KS, A, B, WM, WN, NPL, XVEC, CAL, NST, MAXR)                                     \
-    {KS, A, B, WM, WN, NPL, XVEC, CAL, NST, MAXR,                                               \
-     &launch_igemm<KS, A, B, WM, WN, NPL, XVEC, (CAL != 0), NST, MAXR>}
+    {KS, A, B, WM, WN, NPL, XVEC, CAL, HGC_IGEMM_PACKED, NST, MAXR,                             \
+     &launch_igemm<KS, A, B, WM, WN, NPL, XVEC, (CAL != 0), (HGC_IGEMM_PACKED != 0), NST, MAXR>}
 // aligned-channel forms of one tile shape for input loads of 8, 4, 2 and 1 pixels
 #define HGC_VX(KS, A, B, WM, WN, NPL, NST, R8, R4, R2, R1)                                      \
     HGC_V1(KS, A, B, WM, WN, NPL, 8, 1, NST, R8), HGC_V1(KS, A, B, WM, WN, NPL, 4, 1, NST, R4), \
@@ -593,22 +624,26 @@ static hipError_t launch_igemm(const ConvArgs &a, size_t lds, hipStream_t stream
 static const IgemmVariant g_variants[] = {
     //     KS  A  B  WM WN NPL NST  patch rounds in registers per input-load width
     HGC_VX(3, 2, 4, 2, 4, 2, 2, 1, 1, 2, 2),    // 128 ch x 512 px, 8 waves: throughput tile
+    HGC_VX(3, 4, 2, 2, 4, 2, 2, 1, 1, 1, 2),    // 256 ch x 256 px, 8 waves
     HGC_VX(3, 2, 4, 2, 2, 2, 2, 1, 2, 2, 4),    // 128 ch x 256 px
+    HGC_VX(3, 2, 2, 2, 2, 2, 2, 1, 1, 2, 2),    // 128 ch x 128 px
     HGC_VX(3, 2, 2, 1, 4, 2, 2, 1, 1, 2, 4),    //  64 ch x 256 px
     HGC_VR(3, 2, 2, 1, 4, 2, 2, 2, 4),
-    HGC_VX(3, 2, 2, 1, 2, 4, 2, 1, 2, 2, 3),    //  64 ch x 128 px, 32 channels per step: latency tile
-    HGC_VX(3, 1, 2, 1, 2, 4, 2, 1, 2, 2, 4),    //  32 ch x 128 px
-    HGC_VR(3, 1, 2, 1, 2, 4, 2, 2, 4),
+    HGC_VX(3, 2, 1, 1, 4, 4, 2, 1, 1, 2, 2),    //  64 ch x 128 px, 32 channels per step
+    HGC_VX(3, 1, 2, 2, 2, 4, 2, 1, 1, 2, 2),    //  64 ch x 128 px, waves 2 x 2
+    HGC_VX(3, 1, 2, 1, 4, 2, 2, 1, 1, 2, 4),    //  32 ch x 256 px
+    HGC_VX(3, 1, 1, 1, 4, 4, 2, 1, 1, 2, 2),    //  32 ch x 128 px, 32 channels per step
+    HGC_VR(3, 1, 2, 1, 4, 2, 2, 2, 4),
     HGC_VX(1, 2, 4, 2, 2, 8, 2, 1, 1, 2, 4),    // pointwise 128 ch x 256 px, 64 channels per step
     HGC_VX(1, 2, 2, 1, 4, 8, 2, 1, 1, 2, 4),    // pointwise  64 ch x 256 px
     HGC_VR(1, 2, 2, 1, 4, 8, 2, 2, 4),
-    HGC_VX(1, 2, 2, 1, 2, 8, 2, 1, 2, 2, 4),    // pointwise  64 ch x 128 px
+    HGC_VX(1, 2, 1, 1, 4, 8, 2, 1, 1, 2, 4),    // pointwise  64 ch x 128 px
     HGC_VX(5, 2, 2, 1, 4, 2, 1, 1, 2, 3, 4),    // 5x5  64 ch x 256 px
     HGC_VR(5, 2, 2, 1, 4, 2, 1, 3, 4),
     HGC_VR(7, 1, 2, 1, 4, 2, 1, 3, 6),          // stem-like 7x7: 32 ch x 256 px
 };
 
-const IgemmVariant *igemm_variants(int *count)
+const IgemmVariant *HGC_IGEMM_ACCESSOR(int *count)
 {
     *count = (int)(sizeof(g_variants) / sizeof(g_variants[0]));
     return g_variants;

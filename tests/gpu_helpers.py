@@ -20,14 +20,22 @@ def to_dev(a):
     return torch.from_numpy(np.ascontiguousarray(a)).cuda()
 
 
-def run_layer(L, x, w, b, use_ws=False, poison=True):
-    """One call through hgc_conv2d_forward(_ws). Returns y as a numpy float16 array."""
+def run_layer(L, x, w, b, use_ws=False, poison=True, packed=False):
+    """One call through hgc_conv2d_forward(_ws|_packed). Returns y as a numpy float16 array."""
     import torch
     xd, wd, bd = to_dev(x), to_dev(w), to_dev(b)
     y = torch.empty(L.y_shape, dtype=torch.float16, device="cuda")
     if poison:
         y.view(torch.int16).fill_(0x7E00)          # NaN bit pattern: unwritten outputs show up
-    if use_ws:
+    if packed:
+        wp = torch.empty(hgc.conv2d_packed_weights_size(L), dtype=torch.uint8, device="cuda")
+        wp.fill_(0x7E)                              # every byte is overwritten by the pack kernel
+        hgc.conv2d_pack_weights(L, wd, wp)
+        need = hgc.conv2d_workspace_size(L)
+        ws = torch.empty(max(need, 1), dtype=torch.uint8, device="cuda")
+        ws.fill_(0xFF)
+        hgc.conv2d_forward_packed(L, xd, wp, bd, y, ws)
+    elif use_ws:
         need = hgc.conv2d_workspace_size(L)
         ws = None
         if need:

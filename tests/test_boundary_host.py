@@ -93,14 +93,31 @@ def test_workspace_is_checked_before_any_launch(lib):
     assert need >= plan.workspace_bytes == 4 * plan.split_k * 512 * 14 * 14
     d = ConvDesc.make(L)
     assert hgc.forward_ws_raw(d, FAKE, FAKE, FAKE, FAKE, 0, 0) == -4
-    assert hgc.forward_ws_raw(d, FAKE, FAKE, FAKE, FAKE, FAKE, need - 1) == -4
+    # FAKE is 16-byte aligned, so the call plans like hgc_conv2d_plan does
+    assert hgc.forward_ws_raw(d, FAKE, FAKE, FAKE, FAKE, FAKE, plan.workspace_bytes - 1) == -4
     # the workspace-free entry never needs one
     assert hgc.conv2d_plan(L, with_workspace=False).workspace_bytes == 0
 
 
+def test_packed_entry_points_validate_on_the_host(lib):
+    L = ConvLayer("pk", 1, 20, 9, 9, 12, 3, 1, 1, 2)
+    size = hgc.conv2d_packed_weights_size(L)
+    raw = 2 * 12 * 10 * 9
+    units = 2 * 1 * 2 * 9 * 8 * 16
+    assert size == (raw + 255) // 256 * 256 + (units + 255) // 256 * 256 + 1024
+    d = ConvDesc.make(L)
+    assert lib.hgc_conv2d_pack_weights(ctypes.byref(d), None, ctypes.c_void_p(FAKE), None) == -1
+    assert lib.hgc_conv2d_pack_weights(ctypes.byref(d), ctypes.c_void_p(FAKE), ctypes.c_void_p(FAKE + 16), None) == -6
+    assert hgc.forward_packed_raw(d, FAKE, 0, FAKE, FAKE, 0, 0) == -1
+    assert hgc.forward_packed_raw(d, FAKE, FAKE + 16, FAKE, FAKE, 0, 0) == -6
+    assert hgc.forward_packed_raw(_d(stride=0), FAKE, FAKE, FAKE, FAKE, 0, 0) == -2
+    p = hgc.conv2d_plan(L, True, packed=True)
+    assert p.path in hgc.PATH_NAMES
+
+
 def test_status_strings(lib):
-    seen = {hgc.status_string(s) for s in (0, -1, -2, -3, -4, -5)}
-    assert len(seen) == 6 and hgc.status_string(0) == "ok"
+    seen = {hgc.status_string(s) for s in (0, -1, -2, -3, -4, -5, -6)}
+    assert len(seen) == 7 and hgc.status_string(0) == "ok"
     assert hgc.status_string(-99) == "unknown status"
     assert hgc.version() >= 100
 

@@ -62,11 +62,11 @@ def _layer(t, bias=1, relu=1):
 
 @pytest.mark.parametrize("t", SHAPES)
 def test_shapes_full_tensor(oracle, t):
-    for bias, relu, ws in [(1, 1, False), (0, 0, True)]:
+    for bias, relu, ws, packed in [(1, 1, False, False), (0, 0, True, False), (1, 0, True, True)]:
         L = _layer(t, bias, relu)
-        say(f"[case] {L} ws={ws} plan={hgc.conv2d_plan(L, ws).as_dict()}")
+        say(f"[case] {L} ws={ws} packed={packed} plan={hgc.conv2d_plan(L, ws, packed).as_dict()}")
         x, w, b = make_tensors(L, seed=100 + bias)
-        y = run_layer(L, x, w, b, use_ws=ws)
+        y = run_layer(L, x, w, b, use_ws=ws, packed=packed)
         assert_full(oracle, L, x, w, b, y)
 
 
@@ -79,11 +79,11 @@ def test_integer_inputs_are_exact(oracle, t):
             pytest.skip("sums leave the exact range")
     else:
         x, w, b = make_integer_tensors(L, seed=7)
-    for ws in (False, True):
-        say(f"[int] {L} ws={ws}")
-        y = run_layer(L, x, w, b, use_ws=ws)
-        pre, _ = oracle.conv2d_forward(L.desc(), x, w, b)
-        assert np.array_equal(y.astype(np.float64), pre), f"{L} ws={ws}"
+    pre, _ = oracle.conv2d_forward(L.desc(), x, w, b)
+    for ws, packed in ((False, False), (True, False), (True, True)):
+        say(f"[int] {L} ws={ws} packed={packed}")
+        y = run_layer(L, x, w, b, use_ws=ws, packed=packed)
+        assert np.array_equal(y.astype(np.float64), pre), f"{L} ws={ws} packed={packed}"
 
 
 def test_every_tile_variant_agrees_with_the_oracle(oracle):
@@ -93,23 +93,26 @@ def test_every_tile_variant_agrees_with_the_oracle(oracle):
               5: (1, 16, 18, 20, 96, 5, 1, 2, 1), 7: (1, 8, 18, 20, 48, 7, 1, 3, 1)}
     seen = 0
     try:
-        for v in range(64):
-            for k, t in probes.items():
-                L = _layer(t)
-                hgc.set_forced_path(hgc.PATH_IGEMM, v)
-                p = hgc.conv2d_plan(L, False)
-                if p.path != hgc.PATH_IGEMM or p.variant != v:
-                    continue
-                seen += 1
-                for ws in (False, True):
-                    hgc.set_forced_path(hgc.PATH_IGEMM_SPLITK if ws else hgc.PATH_IGEMM, v)
-                    say(f"[variant {v}] {L} ws={ws} plan={hgc.conv2d_plan(L, ws).as_dict()}")
-                    x, w, b = make_tensors(L, seed=v)
-                    y = run_layer(L, x, w, b, use_ws=ws)
-                    assert_full(oracle, L, x, w, b, y, tag=f"variant {v}")
+        for packed in (False, True):
+            for v in range(128):
+                for k, t in probes.items():
+                    L = _layer(t)
+                    hgc.set_forced_path(hgc.PATH_IGEMM, v)
+                    p = hgc.conv2d_plan(L, packed, packed)
+                    if p.path != hgc.PATH_IGEMM or p.variant != v:
+                        continue
+                    seen += 1
+                    for ws in (False, True):
+                        if packed and not ws:
+                            continue
+                        hgc.set_forced_path(hgc.PATH_IGEMM_SPLITK if ws else hgc.PATH_IGEMM, v)
+                        say(f"[variant {v} packed={packed}] {L} ws={ws} plan={hgc.conv2d_plan(L, ws, packed).as_dict()}")
+                        x, w, b = make_tensors(L, seed=v)
+                        y = run_layer(L, x, w, b, use_ws=ws, packed=packed)
+                        assert_full(oracle, L, x, w, b, y, tag=f"variant {v} packed={packed}")
     finally:
         hgc.set_forced_path(hgc.PATH_AUTO)
-    assert seen >= 12
+    assert seen >= 60
 
 
 def test_direct_and_mfma_paths_agree(oracle):
@@ -155,16 +158,12 @@ def test_configs_batch1_full_tensor(oracle, cfg):
     worst = 0.0
     for i, L in enumerate(CONFIGS[cfg](1)):
         x, w, b = make_tensors(L, seed=layer_seed(cfg, i))
-        for ws in (False, True):
-            say(f"[{cfg}] {L.name} ws={ws} plan={hgc.conv2d_plan(L, ws).as_dict()}")
-            y = run_layer(L, x, w, b, use_ws=ws)
-            if ws:
-                pre, mag = cached
-            else:
-                pre, mag = oracle.conv2d_forward(L.desc(), x, w, b)
-                cached = (pre, mag)
+        pre, mag = oracle.conv2d_forward(L.desc(), x, w, b)
+        for ws, packed in ((False, False), (True, False), (True, True)):
+            say(f"[{cfg}] {L.name} ws={ws} packed={packed} plan={hgc.conv2d_plan(L, ws, packed).as_dict()}")
+            y = run_layer(L, x, w, b, use_ws=ws, packed=packed)
             ok, ratio, where = oracle.check(y, pre, mag, L.relu)
-            assert ok, f"{L} ws={ws}: |err|/bound={ratio:.3g} at {where}"
+            assert ok, f"{L} ws={ws} packed={packed}: |err|/bound={ratio:.3g} at {where}"
             worst = max(worst, ratio)
     say(f"[{cfg}] worst |err|/bound = {worst:.3f}")
     assert worst <= 1.0
@@ -177,8 +176,33 @@ def test_configs_full_batch_sampled(oracle, cfg, N):
     rng = np.random.default_rng(1234)
     for i, L in enumerate(CONFIGS[cfg](N)):
         x, w, b = make_tensors(L, seed=layer_seed(cfg, i))
-        say(f"[{cfg} N={N}] {L.name} plan={hgc.conv2d_plan(L, True).as_dict()}")
-        y = run_layer(L, x, w, b, use_ws=True)
         idx = sample_points(L, rng, 4000)
-        assert_points(oracle, L, x, w, b, y, idx)
-        assert np.isfinite(y.astype(np.float32)).all()
+        for packed in (True, False):
+            say(f"[{cfg} N={N}] {L.name} packed={packed} plan={hgc.conv2d_plan(L, True, packed).as_dict()}")
+            y = run_layer(L, x, w, b, use_ws=True, packed=packed)
+            assert_points(oracle, L, x, w, b, y, idx)
+            assert np.isfinite(y.astype(np.float32)).all()
+
+
+def test_packed_buffer_holds_the_weights_verbatim_and_zero_padding():
+    """The pack kernel is pure data movement: check every byte it writes."""
+    import torch
+    L = _layer((1, 20, 9, 9, 12, 3, 1, 1, 2))            # Cg = 10, Mg = 6: ragged in both directions
+    _, w, _ = make_tensors(L, seed=5)
+    wd = torch.from_numpy(w).cuda()
+    wp = hgc.conv2d_pack_weights(L, wd).cpu().numpy()
+    raw = wp[:w.size * 2].view(np.float16).reshape(w.shape)
+    assert np.array_equal(raw.view(np.uint16), w.view(np.uint16))
+    T, Mg, Cg, G = 9, 6, 10, 2
+    MB8, NP8 = 1, 2
+    off = (w.size * 2 + 255) // 256 * 256
+    assert not wp[w.size * 2:off].any()
+    units = wp[off:off + G * MB8 * NP8 * T * 8 * 16].view(np.float16).reshape(G, MB8, NP8, T, 8, 8)
+    want = np.zeros_like(units)
+    wg = w.reshape(G, Mg, Cg, T)
+    for g in range(G):
+        for m in range(Mg):
+            for c in range(Cg):
+                want[g, m // 8, c // 8, :, m % 8, c % 8] = wg[g, m, c, :]
+    assert np.array_equal(units.view(np.uint16), want.view(np.uint16))
+    assert not wp[off + units.size * 2:].any() and wp.size == hgc.conv2d_packed_weights_size(L)
