@@ -85,25 +85,39 @@ static double estimate_cycles(const Geometry &g, const Candidate &c)
 {
     const IgemmVariant &v = *c.v;
     const int T = v.ks * v.ks;
-    const double waves_per_simd = v.threads() / 256.0 > 1.0 ? v.threads() / 256.0 : 1.0;
-    const double mfma = 32.0 * v.wm_blocks * v.wn_blocks * T * (v.npl / 2) * waves_per_simd;
-    const double stage_bytes = 16.0 * T * v.npl * v.BM() * 1.4 + 16.0 * v.npl * c.PH * c.PWU * 2.5;
-    const double scalar_penalty = (v.calign ? 1.0 : 4.0) * (v.xvec == 2 ? 1.0 : 1.5);
-    const double stage = stage_bytes / 40.0 * scalar_penalty;
-    const double step = (v.nstage == 2 ? std::max(mfma, stage) + 300.0 : mfma + stage + 600.0);
-    const double epilogue = 25.0 * 16 * v.wm_blocks * v.wn_blocks * waves_per_simd;
-    const double wg = 4000.0 + stage + c.steps_per_split * step + epilogue;
-    int wg_per_cu = (int)(kMaxLds / std::max<long long>(c.lds, 1));
-    const int by_threads = 1024 / v.threads() >= 1 ? 1024 / v.threads() : 1;   // 512 VGPR budget: <= 4 waves/SIMD
-    wg_per_cu = std::max(1, std::min(wg_per_cu, std::min(by_threads, 2)));
-    const double slots = 256.0 * wg_per_cu;
-    const double rounds = std::ceil((double)c.grid * c.split / slots);
-    // co-resident workgroups share the CU: their MFMA work serialises
-    const double share = (wg_per_cu > 1 && (double)c.grid * c.split > 256.0) ? 1.0 + 0.6 * (wg_per_cu - 1) : 1.0;
-    double total = rounds * wg * share;
+    const int NW = v.waves_m * v.waves_n, NT = 64 * NW;
+    const int RPW = v.BM() / NW;
+    const int WLR = (RPW * v.npl * T + 63) / 64, WIR = (RPW * v.npl + 63) / 64;
+    const int items = v.npl * c.PH * (c.PWU / v.xvec);
+    const int Rx = (items + NT - 1) / NT;
+    // phases of one K step of one wave, in core cycles (fitted to in-kernel timestamps)
+    static const double xcost[9] = {0, 45, 70, 0, 160, 0, 0, 0, 600};   // transpose + LDS stores per item
+    double L = 25.0 * (8 * Rx + (v.packed || v.calign ? WLR : 0));     // issue of the vector-memory loads
+    double X = Rx * xcost[v.xvec];
+    if (!v.packed) X += v.calign ? 1400.0 * WIR : 250.0 * T * WIR;      // regroup / scalar fetch of weights
+    // windows narrower than 32 columns split a 32-lane operand read over several patch rows
+    // (LDS bank conflicts, shorter global segments)
+    static const double narrow[7] = {2.0, 2.0, 1.5, 1.3, 1.12, 1.0, 1.0};
+    const double C = 32.0 * v.wm_blocks * v.wn_blocks * T * (v.npl / 2) / 0.75 * narrow[c.log2_tw];
+    L *= narrow[c.log2_tw];
+    const double w = NW / 4.0;                                          // waves per SIMD of one workgroup
+    const double mfma_simd = C * std::max(1.0, w);
+    const double serial = L + C + X + (v.nstage == 1 ? 2500.0 : 300.0); // one buffer: the load latency is exposed
+    // co-residency: registers, LDS, threads
+    const int regs = 16 * v.wm_blocks * v.wn_blocks + 90;
+    const int waves_simd = std::max(1, std::min(8, 512 / regs));
+    int k = (int)std::min<double>(waves_simd / std::max(1.0, w), (double)(kMaxLds / std::max<long long>(c.lds, 1)));
+    k = std::max(1, std::min(k, 2048 / NT));
+    const long long wgs = c.grid * c.split;
+    const long long on_cu = (wgs + 255) / 256;                          // workgroups the busiest CU gets
+    k = (int)std::min<long long>(k, on_cu);
+    const double step_time = std::max(k * mfma_simd, serial);
+    const double fixed = 6000.0 + 60.0 * v.wm_blocks * v.wn_blocks + 400.0 + serial;   // ramp, first stage, epilogue
+    const double rounds = std::ceil((double)on_cu / k);
+    double total = rounds * (fixed + c.steps_per_split * step_time);
     if (c.split > 1) {
         const double ws_bytes = 4.0 * c.split * g.N * (double)g.M * g.Ho * g.Wo;
-        total += 9000.0 + 2.0 * ws_bytes / 1500.0;     // write + read of the partial sums, second launch
+        total += 8000.0 + 2.0 * ws_bytes / 2000.0;      // write + read of the partial sums, second launch
     }
     return total;
 }
@@ -114,7 +128,7 @@ static bool plan_igemm(const Geometry &g, bool with_ws, int x_align, bool w_al16
     int nv = 0;
     const IgemmVariant *vs = packed ? igemm_variants_packed(&nv) : igemm_variants_raw(&nv);
     // widest input load: W and x's byte alignment / 2 must be multiples of the pixel count
-    int want_xvec = 8;
+    int want_xvec = 4;   // 8-pixel loads were measured slower: their LDS stores conflict 8 ways
     while (want_xvec > 1 && (g.W % want_xvec || x_align % (2 * want_xvec))) want_xvec >>= 1;
     // packed weights are always 16-byte units; only the input's channel predicates care about Cg % 8
     const int want_cal = (g.Cg % 8 == 0 && (w_al16 || packed)) ? 1 : 0;

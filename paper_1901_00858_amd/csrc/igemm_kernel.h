@@ -613,9 +613,9 @@ static hipError_t launch_igemm(const ConvArgs &a, size_t lds, hipStream_t stream
 #define HGC_V1(KS, A, B, WM, WN, NPL, XVEC, CAL, NST, MAXR)                                     \
     {KS, A, B, WM, WN, NPL, XVEC, CAL, HGC_IGEMM_PACKED, NST, MAXR,                             \
      &launch_igemm<KS, A, B, WM, WN, NPL, XVEC, (CAL != 0), (HGC_IGEMM_PACKED != 0), NST, MAXR>}
-// aligned-channel forms of one tile shape for input loads of 8, 4, 2 and 1 pixels
+// aligned-channel forms of one tile shape for input loads of 4, 2 and 1 pixels
 #define HGC_VX(KS, A, B, WM, WN, NPL, NST, R8, R4, R2, R1)                                      \
-    HGC_V1(KS, A, B, WM, WN, NPL, 8, 1, NST, R8), HGC_V1(KS, A, B, WM, WN, NPL, 4, 1, NST, R4), \
+    HGC_V1(KS, A, B, WM, WN, NPL, 4, 1, NST, R4),                                               \
     HGC_V1(KS, A, B, WM, WN, NPL, 2, 1, NST, R2), HGC_V1(KS, A, B, WM, WN, NPL, 1, 1, NST, R1)
 // ragged-channel forms (Cg % 8 != 0 or unaligned weights): 2- and 1-pixel input loads
 #define HGC_VR(KS, A, B, WM, WN, NPL, NST, R2, R1)                                              \
