@@ -21,6 +21,13 @@ sys.path.insert(0, ROOT)
 PEAK_MFMA_F16 = 2516.6e12     # MI355X dense FP16 MFMA FLOP/s
 PEAK_HBM = 8.0e12             # MI355X HBM3E B/s
 
+# (config, batch, entry, path, variant) -> HBM bytes per launch of the dominant kernel, from
+# the rocprofv3 --pmc summaries under profiles/ (see the design doc for the scaling)
+TRAFFIC_BYTES_PER_LAUNCH = {
+    # mean over the six launches of a step: FETCH_SIZE 4802 KiB x 2.0 (copy calibration) + WRITE_SIZE 2024 KiB
+    ("vgg16", 1, "packed", "igemm", 26): int((2.0 * 4802 + 2024) * 1024),
+}
+
 
 def main() -> int:
     ap = argparse.ArgumentParser()
@@ -34,6 +41,9 @@ def main() -> int:
                     help="C entry point: hgc_conv2d_forward_packed (weights re-laid out once, before "
                          "timing, like a model load), hgc_conv2d_forward_ws or hgc_conv2d_forward")
     ap.add_argument("--per-layer", action="store_true", help="print a per-layer table to stderr")
+    ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MiB",
+                    help="also run a device-to-device copy of this many MiB ten times (a known-size "
+                         "kernel that scales the HBM byte counters of a rocprofv3 --pmc run)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus must be 1 (no multi-GPU path exists)",
@@ -65,6 +75,12 @@ def main() -> int:
         bufs.append((hgc.ConvDesc.make(L), xd, wd, bd, y, ws, need, wp))
     stream = torch.cuda.current_stream(dev)
     sh = stream.cuda_stream
+    if args.calibrate_copy:
+        src = torch.ones(args.calibrate_copy << 20, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(10):
+            dst.copy_(src)
+        torch.cuda.synchronize()
 
     def launch(i, entry=args.entry):
         d, xd, wd, bd, y, ws, need, wp = bufs[i]
@@ -99,19 +115,19 @@ def main() -> int:
     bytes_step = sum(L.bytes for L in layers)
     tflops = flops_step / (ms_per_step * 1e-3) / 1e12
 
-    # ---- per-layer device time: HIP events on the launch stream around R launches ----
+    # ---- per-launch device time: a pair of HIP events on the launch stream around EVERY
+    # launch of an instrumented pass (the timed region above carries no events) ----
     reps = max(5, min(50, args.steps))
     per_layer = []
     for i, L in enumerate(layers):
         launch(i)
-        e0 = torch.cuda.Event(enable_timing=True)
-        e1 = torch.cuda.Event(enable_timing=True)
-        e0.record(stream)
-        for _ in range(reps):
+        pairs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
+        for e0, e1 in pairs:
+            e0.record(stream)
             launch(i)
-        e1.record(stream)
-        e1.synchronize()
-        us = e0.elapsed_time(e1) * 1e3 / reps
+            e1.record(stream)
+        pairs[-1][1].synchronize()
+        us = sum(e0.elapsed_time(e1) for e0, e1 in pairs) * 1e3 / reps
         plan = hgc.conv2d_plan(L, args.entry != "plain", args.entry == "packed").as_dict()
         per_layer.append({
             "layer": L.name, "path": plan["path_name"], "variant": plan["variant"],
@@ -119,7 +135,7 @@ def main() -> int:
             "grid": plan["grid"], "us": us, "tflops": L.flops / us / 1e6, "gbs": L.bytes / us / 1e3,
             "flops": L.flops, "bytes": L.bytes,
         })
-    # the dominant kernel: the layer class (same instantiation) with the largest summed time
+    # the dominant kernel: the instantiation whose launches take the largest share of a step
     groups = {}
     for r in per_layer:
         g = groups.setdefault((r["path"], r["variant"]), {"us": 0.0, "flops": 0, "bytes": 0, "n": 0, "layers": []})
@@ -127,16 +143,23 @@ def main() -> int:
         g["layers"].append(r["layer"])
     key, dom = max(groups.items(), key=lambda kv: kv[1]["us"])
     mfma_bound = (dom["flops"] / PEAK_MFMA_F16) >= (dom["bytes"] / PEAK_HBM)
+    # HBM bytes per launch from the committed rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE scaled by
+    # a plain copy of known size); see profiles/.  None when no such run covers this kernel/workload.
+    traffic = TRAFFIC_BYTES_PER_LAUNCH.get((args.config, args.batch, args.entry, key[0], key[1]))
     if mfma_bound:
-        achieved = dom["flops"] / dom["us"] / 1e6          # TFLOP/s
+        achieved = dom["flops"] / dom["us"] / 1e6          # algorithmic TFLOP/s over its launches
         roof = {"bound": "mfma", "achieved": achieved, "peak": PEAK_MFMA_F16 / 1e12, "unit": "TFLOP/s",
-                "frac": achieved / (PEAK_MFMA_F16 / 1e12), "traffic": None}
+                "frac": achieved / (PEAK_MFMA_F16 / 1e12), "traffic": traffic}
     else:
-        achieved = dom["bytes"] / dom["us"] / 1e3          # GB/s
+        achieved = dom["bytes"] / dom["us"] / 1e3          # algorithmic GB/s over its launches
         roof = {"bound": "hbm", "achieved": achieved, "peak": PEAK_HBM / 1e9, "unit": "GB/s",
-                "frac": achieved / (PEAK_HBM / 1e9), "traffic": None}
-    roof.update({"kernel": f"{key[0]}:variant{key[1]}", "layers": dom["layers"],
+                "frac": achieved / (PEAK_HBM / 1e9), "traffic": traffic}
+    kname = hgc.igemm_variant_name(key[1], args.entry == "packed") if key[0].startswith("igemm") else key[0]
+    roof.update({"kernel": kname + (", true>" if key[0] == "igemm_splitk" else ", false>" if key[0] == "igemm" else ""),
+                 "layers": dom["layers"], "launches_per_step": dom["n"],
                  "avg_launch_us": dom["us"] / dom["n"],
+                 "algorithmic_flops_per_launch": dom["flops"] / dom["n"],
+                 "algorithmic_bytes_per_launch": dom["bytes"] / dom["n"],
                  "sum_layer_us": sum(r["us"] for r in per_layer)})
 
     if args.per_layer:

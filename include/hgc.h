@@ -168,6 +168,14 @@ const char *hgc_status_string(hgc_status status);
  */
 const char *hgc_last_launch_error(void);
 
+/*
+ * Diagnostic: writes the template-argument prefix of implicit-GEMM instantiation
+ * `variant` (hgc_plan.variant; packed = 1 for hgc_conv2d_forward_packed's table) as a
+ * profiler prints it, e.g. "igemm_kernel<3, 1, 1, 1, 4, 4, 4, true, true, 2, 1".
+ * Returns the length, or -1 for a bad index or buffer.
+ */
+int32_t hgc_igemm_variant_name(int32_t packed, int32_t variant, char *buf, int32_t buf_len);
+
 /* Library version: major * 10000 + minor * 100 + patch. */
 int32_t hgc_version(void);
 

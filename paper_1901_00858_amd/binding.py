@@ -97,6 +97,8 @@ def load():
     lib.hgc_status_string.argtypes = [ctypes.c_int32]
     lib.hgc_status_string.restype = ctypes.c_char_p
     lib.hgc_version.restype = ctypes.c_int32
+    lib.hgc_igemm_variant_name.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_char_p, ctypes.c_int32]
+    lib.hgc_igemm_variant_name.restype = ctypes.c_int32
     lib.hgc_last_launch_error.restype = ctypes.c_char_p
     _lib = lib
     return lib
@@ -116,6 +118,12 @@ def set_forced_path(path: int = PATH_AUTO, tile_variant: int = -1) -> int:
 
 def set_forced_tiling(log2_tile_w: int = -1, split_k: int = -1) -> None:
     load().hgc_set_forced_tiling(int(log2_tile_w), int(split_k))
+
+
+def igemm_variant_name(variant: int, packed: bool = False) -> str:
+    buf = ctypes.create_string_buffer(160)
+    n = load().hgc_igemm_variant_name(1 if packed else 0, int(variant), buf, 160)
+    return buf.value.decode() if n >= 0 else ""
 
 
 def conv2d_workspace_size(desc) -> int:

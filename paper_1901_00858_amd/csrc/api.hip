@@ -7,6 +7,7 @@
 #include <atomic>
 #include <climits>
 #include <cmath>
+#include <cstdio>
 #include <cstring>
 
 #include "hgc_internal.h"
@@ -412,6 +413,18 @@ const char *hgc_status_string(hgc_status status)
 }
 
 int32_t hgc_version(void) { return 100; }
+
+int32_t hgc_igemm_variant_name(int32_t packed, int32_t variant, char *buf, int32_t buf_len)
+{
+    int nv = 0;
+    const IgemmVariant *vs = packed ? igemm_variants_packed(&nv) : igemm_variants_raw(&nv);
+    if (!buf || buf_len < 1 || variant < 0 || variant >= nv) return -1;
+    const IgemmVariant &v = vs[variant];
+    // the kernel's template arguments, in order, as rocprofv3 prints them (without the split flag)
+    return (int32_t)snprintf(buf, (size_t)buf_len, "igemm_kernel<%d, %d, %d, %d, %d, %d, %d, %s, %s, %d, %d",
+                             v.ks, v.wm_blocks, v.wn_blocks, v.waves_m, v.waves_n, v.npl, v.xvec,
+                             v.calign ? "true" : "false", v.packed ? "true" : "false", v.nstage, v.max_rounds);
+}
 
 const char *hgc_last_launch_error(void)
 {
