@@ -99,8 +99,121 @@ __global__ __launch_bounds__(256) void depthwise_kernel(const ConvArgs p)
     }
 }
 
+// Depthwise 3x3, pad 1, vector form.  A thread produces RO rows x VO consecutive outputs
+// from RO*STRIDE + 3 - STRIDE input rows; each input row is one aligned load of
+// VI = VO*STRIDE pixels, and the two halo columns come from the neighbouring lanes by
+// wavefront shuffles (lanes run along the row).  Only the first and last lane of a wave,
+// when their neighbour pixel belongs to another wave, fetch the halo themselves.
+// x and y are each touched once (rows shared by vertically adjacent threads hit in cache).
+template <int STRIDE, int VO, int RO>
+__global__ __launch_bounds__(256) void depthwise3_vec_kernel(const ConvArgs p)
+{
+    constexpr int VI = VO * STRIDE;
+    constexpr int RI = (RO - 1) * STRIDE + 3;      // input rows per thread
+    typedef uint16_t hv __attribute__((ext_vector_type(VI)));
+    typedef uint16_t ho __attribute__((ext_vector_type(VO)));
+    const int GW = p.Wo / VO;                      // thread groups per output row
+    const int GH = (p.Ho + RO - 1) / RO;           // row groups per plane
+    const long long items = (long long)p.N * p.C * GH * GW;
+    const int lane = threadIdx.x & 63;
+    for (long long t = (long long)blockIdx.x * 256 + threadIdx.x; t - lane < items;
+         t += (long long)gridDim.x * 256) {
+        const bool live = t < items;               // whole waves stay in the loop: shuffles need every lane
+        const long long tt = live ? t : items - 1;
+        const int owg = (int)(tt % GW);
+        const long long u = tt / GW;
+        const int oh0 = (int)(u % GH) * RO;
+        const long long nc = u / GH;
+        const int c = (int)(nc % p.C);
+        float wr[9];
+#pragma unroll
+        for (int k = 0; k < 9; ++k) wr[k] = h2f(p.w[(size_t)c * 9 + k]);
+        const float bv = p.bias ? h2f(p.b[c]) : 0.0f;
+        float acc[RO][VO];
+#pragma unroll
+        for (int o = 0; o < RO; ++o)
+#pragma unroll
+            for (int j = 0; j < VO; ++j) acc[o][j] = bv;
+        const uint16_t *xp = p.x + (size_t)nc * p.H * p.W;
+        const int iw0 = owg * VI;                  // first input column of the vector; the window starts at iw0 - 1
+#pragma unroll
+        for (int rr = 0; rr < RI; ++rr) {
+            const int ih = oh0 * STRIDE - 1 + rr;
+            const bool row_ok = live && ih >= 0 && ih < p.H;
+            float in[VI + 2];                      // columns iw0-1 .. iw0+VI
+            hv v;
+#pragma unroll
+            for (int j = 0; j < VI; ++j) v[j] = 0;
+            if (row_ok) v = *reinterpret_cast<const hv *>(xp + (size_t)ih * p.W + iw0);
+#pragma unroll
+            for (int j = 0; j < VI; ++j) in[j + 1] = h2f(v[j]);
+            // halo columns: the neighbour lane holds the adjacent vector of the same row
+            float left = __shfl_up(in[VI], 1);
+            float right = __shfl_down(in[1], 1);
+            if (owg == 0) left = 0.0f;             // padding column
+            else if (lane == 0) left = row_ok ? h2f(xp[(size_t)ih * p.W + iw0 - 1]) : 0.0f;
+            if (STRIDE == 1) {
+                if (owg == GW - 1) right = 0.0f;
+                else if (lane == 63) right = row_ok ? h2f(xp[(size_t)ih * p.W + iw0 + VI]) : 0.0f;
+            }
+            in[0] = left;
+            in[VI + 1] = right;
+            // input row rr is tap row kr of output row o when rr = o*STRIDE + kr
+#pragma unroll
+            for (int kr = 0; kr < 3; ++kr) {
+                if (rr - kr < 0 || (rr - kr) % STRIDE != 0 || (rr - kr) / STRIDE >= RO) continue;
+                const int o = (rr - kr) / STRIDE;
+#pragma unroll
+                for (int j = 0; j < VO; ++j)
+#pragma unroll
+                    for (int q = 0; q < 3; ++q)
+                        acc[o][j] = fmaf(wr[kr * 3 + q], in[j * STRIDE + q], acc[o][j]);
+            }
+        }
+        if (live) {
+#pragma unroll
+            for (int o = 0; o < RO; ++o) {
+                if (oh0 + o >= p.Ho) continue;
+                ho ov;
+#pragma unroll
+                for (int j = 0; j < VO; ++j) ov[j] = f2h(p.relu ? fmaxf(acc[o][j], 0.0f) : acc[o][j]);
+                *reinterpret_cast<ho *>(p.y + ((size_t)nc * p.Ho + oh0 + o) * p.Wo + owg * VO) = ov;
+            }
+        }
+    }
+}
+
+template <int STRIDE, int VO>
+static hipError_t launch_dw3(const ConvArgs &a, hipStream_t stream)
+{
+    constexpr int RO = (VO >= 8) ? 2 : 4;          // output rows per thread
+    const long long items = (long long)a.N * a.C * ((a.Ho + RO - 1) / RO) * (a.Wo / VO);
+    long long blocks = (items + 255) / 256;
+    if (blocks > 1048576) blocks = 1048576;
+    hipLaunchKernelGGL((depthwise3_vec_kernel<STRIDE, VO, RO>), dim3((unsigned)blocks), dim3(256), 0, stream, a);
+    return hipGetLastError();
+}
+
 hipError_t launch_depthwise(const ConvArgs &a, hipStream_t stream)
 {
+    // vector form: 3x3, pad 1, stride 1 or 2, rows that split into aligned vectors
+    if (a.ks == 3 && a.pad == 1 && (a.stride == 1 || a.stride == 2) && (a.stride == 1 || a.W % 2 == 0)) {
+        const uintptr_t xa = (uintptr_t)a.x, ya = (uintptr_t)a.y;
+        int vi = 8;                                 // input pixels per load
+        while (vi > a.stride && (a.W % vi || xa % (2 * vi) || a.Wo % (vi / a.stride) || ya % (2 * vi / a.stride)))
+            vi >>= 1;
+        if (a.W % vi == 0 && xa % (2 * vi) == 0 && a.Wo % (vi / a.stride) == 0 && ya % (2 * vi / a.stride) == 0) {
+            if (a.stride == 1) {
+                if (vi == 8) return launch_dw3<1, 8>(a, stream);
+                if (vi == 4) return launch_dw3<1, 4>(a, stream);
+                if (vi == 2) return launch_dw3<1, 2>(a, stream);
+                return launch_dw3<1, 1>(a, stream);
+            }
+            if (vi == 8) return launch_dw3<2, 4>(a, stream);
+            if (vi == 4) return launch_dw3<2, 2>(a, stream);
+            if (vi == 2) return launch_dw3<2, 1>(a, stream);
+        }
+    }
     const int chunks = (a.Ho * a.Wo + 255) / 256;
     long long blocks = (long long)a.N * a.C * chunks;
     if (blocks > 1048576) blocks = 1048576;

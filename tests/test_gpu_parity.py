@@ -49,6 +49,12 @@ SHAPES = [
     (2, 24, 19, 19, 24, 3, 1, 1, 24),    # depthwise
     (1, 16, 30, 30, 16, 3, 2, 1, 16),    # depthwise stride 2
     (1, 8, 16, 16, 8, 5, 1, 2, 8),       # depthwise 5x5
+    (2, 16, 24, 32, 16, 3, 1, 1, 16),    # depthwise, 8-pixel vectors, rows end on wave boundaries
+    (1, 8, 9, 56, 8, 3, 1, 1, 8),        # depthwise, 8-pixel vectors, halo fetched across waves
+    (1, 8, 12, 28, 8, 3, 1, 1, 8),       # depthwise, 4-pixel vectors
+    (1, 8, 14, 14, 8, 3, 1, 1, 8),       # depthwise, 2-pixel vectors
+    (1, 8, 10, 112, 8, 3, 2, 1, 8),      # depthwise stride 2, 8-pixel input vectors
+    (2, 8, 28, 28, 8, 3, 2, 1, 8),       # depthwise stride 2, 4-pixel input vectors
     (1, 8, 9, 9, 16, 3, 1, 1, 8),        # channel multiplier 2 (Mg = 2) -> direct
     (1, 16, 33, 70, 32, 3, 1, 1, 1),     # several window tiles in both directions
     (1, 16, 3, 3, 32, 3, 1, 0, 1),       # single output pixel
