@@ -77,7 +77,9 @@ typedef struct hgc_plan {
     int32_t path;            /* HGC_PATH_*                                              */
     int32_t Ho, Wo;          /* output extent                                           */
     int32_t tile_m;          /* output channels per workgroup                           */
-    int32_t tile_h, tile_w;  /* output pixels per workgroup: tile_h rows x tile_w cols  */
+    int32_t tile_h, tile_w;  /* output pixels per workgroup: tile_h rows x tile_w cols
+                                (1x1 stride-1 unpadded layers: of the image seen as one
+                                row of H*W pixels)                                      */
     int32_t split_k;         /* >= 1; number of reduction slices                        */
     int32_t variant;         /* kernel instantiation index (diagnostic)                 */
     int32_t grid;            /* workgroups of the main kernel                           */

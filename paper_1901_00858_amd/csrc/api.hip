@@ -42,6 +42,7 @@ static hgc_status validate(const hgc_conv2d_desc *d, Geometry *g)
     g->Mg = d->num_output / d->group;
     g->Kg = (long long)g->Cg * g->k * g->k;
     g->P = (long long)g->N * g->Ho * g->Wo;
+    g->flat = false;
     // kernels index tensors with 32-bit element counts
     const long long lim = INT_MAX;
     const long long nx = (long long)g->N * g->C;
@@ -50,6 +51,18 @@ static hgc_status validate(const hgc_conv2d_desc *d, Geometry *g)
     const long long ny = (long long)g->N * g->M;
     if (ny > lim || ny * g->Ho > lim || ny * g->Ho * g->Wo > lim) return HGC_ERR_TOO_LARGE;
     return HGC_OK;
+}
+
+// A 1x1, stride 1, unpadded layer is Y[n] = W * X[n] with X[n] a C x (H*W) row-major matrix:
+// the kernels may treat each image as one row of H*W pixels, which makes every channel's
+// share of a tile one contiguous run in memory.
+static Geometry kernel_geometry(const Geometry &g)
+{
+    Geometry f = g;
+    if (g.k == 1 && g.s == 1 && g.p == 0 && g.H > 1) {
+        f.W = g.H * g.W; f.H = 1; f.Wo = f.W; f.Ho = 1; f.flat = true;
+    }
+    return f;
 }
 
 struct Plan {
@@ -98,7 +111,7 @@ static double estimate_cycles(const Geometry &g, const Candidate &c)
     if (!v.packed) X += v.calign ? 1400.0 * WIR : 250.0 * T * WIR;      // regroup / scalar fetch of weights
     // windows narrower than 32 columns split a 32-lane operand read over several patch rows
     // (LDS bank conflicts, shorter global segments)
-    static const double narrow[7] = {2.0, 2.0, 1.5, 1.3, 1.12, 1.0, 1.0};
+    static const double narrow[10] = {2.0, 2.0, 1.5, 1.3, 1.12, 1.0, 1.0, 1.0, 1.0, 1.0};
     const double C = 32.0 * v.wm_blocks * v.wn_blocks * T * (v.npl / 2) / 0.75 * narrow[c.log2_tw];
     L *= narrow[c.log2_tw];
     const double w = NW / 4.0;                                          // waves per SIMD of one workgroup
@@ -150,7 +163,7 @@ static bool plan_igemm(const Geometry &g, bool with_ws, int x_align, bool w_al16
         const int BN = v.BN();
         const int f_tw = g_forced_log2_tw.load(std::memory_order_relaxed);
         const int f_sp = g_forced_split.load(std::memory_order_relaxed);
-        for (int j = 2; (1 << j) <= BN && j <= 6; ++j) {
+        for (int j = 2; (1 << j) <= BN && j <= 9; ++j) {
             if (f_tw >= 0 && j != f_tw) continue;
             Candidate c;
             c.v = &v;
@@ -202,11 +215,12 @@ static bool plan_igemm(const Geometry &g, bool with_ws, int x_align, bool w_al16
     return true;
 }
 
-static void make_plan(const Geometry &g, bool with_ws, int x_align, bool w_al16, bool packed, Plan *pl)
+static void make_plan(const Geometry &g0, bool with_ws, int x_align, bool w_al16, bool packed, Plan *pl)
 {
+    const Geometry g = kernel_geometry(g0);
     std::memset(pl, 0, sizeof(*pl));
     base_args(g, &pl->args);
-    pl->pub.Ho = g.Ho; pl->pub.Wo = g.Wo;
+    pl->pub.Ho = g0.Ho; pl->pub.Wo = g0.Wo;
     pl->pub.split_k = 1;
     const int forced = g_forced_path.load(std::memory_order_relaxed);
     const int fvar = g_forced_variant.load(std::memory_order_relaxed);
@@ -272,7 +286,8 @@ static hgc_status run(const hgc_conv2d_desc *desc, const void *x, const void *w,
     }
     {   // widest output store: divides Wo and the window width, and y's byte alignment allows it
         int ov = 8;
-        while (ov > 1 && (g.Wo % ov || (1 << a.log2_tw) % ov || ((uintptr_t)y % (2 * ov)))) ov >>= 1;
+        const int wo = kernel_geometry(g).Wo;
+        while (ov > 1 && (wo % ov || (1 << a.log2_tw) % ov || ((uintptr_t)y % (2 * ov)))) ov >>= 1;
         a.out_vec = ov;
     }
     hipStream_t s = static_cast<hipStream_t>(stream);

@@ -16,6 +16,7 @@ struct Geometry {
     int N, C, H, W, M, k, s, p, G, bias, relu;
     int Ho, Wo, Cg, Mg;
     long long Kg, P;
+    bool flat;           // pointwise layer presented to the kernels as 1 x (H*W) images
 };
 
 // Arguments of every kernel: tensors + geometry + the tiling chosen on the host.
@@ -76,7 +77,7 @@ struct IgemmVariant {
     long long lds_bytes(int PH, int PWU) const
     {
         const long long stage = 16LL * (igemm_w_units(ks, wm_blocks, waves_m, waves_n, npl) + npl * PH * PWU + 8);
-        const long long epi = 80LL * 32 * wm_blocks * waves_m * waves_n;
+        const long long epi = 84LL * 32 * wm_blocks * waves_m * waves_n;   // transpose tile + bias per wave
         return nstage * stage > epi ? nstage * stage : epi;
     }
 };

@@ -47,6 +47,11 @@ typedef _Float16 half8 __attribute__((ext_vector_type(8)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) void *lds_ptr_t;
+// the epilogue writes its LDS tile as halves and floats and reads it back as vectors:
+// these accesses must be allowed to alias
+typedef uint16_t __attribute__((may_alias)) u16_alias;
+typedef float __attribute__((may_alias)) f32_alias;
+typedef u32x4 __attribute__((may_alias)) u32x4_alias;
 
 constexpr uint32_t kNoLoad = 0xFFFFFFFFu;       // buffer offset that is always out of range
 
@@ -494,6 +499,13 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void igemm_kernel(const Con
     // ---- epilogue: accumulator register e of lane (l32, lh) in block (i, j) is
     // channel row 8*(e/4) + 4*lh + e%4 and pixel column l32 of that block ----
     const int HoWo = p.Ho * p.Wo;
+    // The last MFMAs may still be in flight.  The compiler pads MFMA -> accumulator-read
+    // hazards along the fall-through path only; a taken branch (for instance around the
+    // bias load) reached the first accumulator read too early and saw it without the last
+    // MFMA's contribution.  32 wait states cover the longest MFMA on any path.
+    __builtin_amdgcn_sched_barrier(0);           // nothing, MFMAs included, moves across the padding
+    asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
+    __builtin_amdgcn_sched_barrier(0);
     if (SPLITK) {
         // FP32 partial sums of this slice: 32 consecutive pixels per row and instruction
 #pragma unroll
@@ -514,17 +526,33 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void igemm_kernel(const Con
     }
     // Bias, ReLU, one rounding to FP16; then each wave transposes its tile through LDS
     // (2-byte writes, 16-byte reads) so that a lane holds 8 consecutive pixels of one
-    // output row and the global stores are 16, 8 or 4 bytes wide.
+    // output row and the global stores are 16, 8 or 4 bytes wide.  Everything that does
+    // not depend on the accumulator block is computed once per wave.
     constexpr int EP = 40;                       // halves per LDS row: 32 pixels + pad (80 bytes)
-    uint16_t *el = reinterpret_cast<uint16_t *>(lds) + wave * (32 * A * EP);
-    float bv[A][16];
+    u16_alias *el = reinterpret_cast<u16_alias *>(lds) + wave * (32 * A * EP);
+    f32_alias *bw = reinterpret_cast<f32_alias *>(reinterpret_cast<u16_alias *>(lds) + NW * (32 * A * EP)) + wave * (32 * A);
+    // the wave's 32*A bias values go through LDS: one load per row instead of one per register
+#pragma unroll
+    for (int r = 0; r < (32 * A + 63) / 64; ++r) {
+        const int row = lane + 64 * r;
+        const int ml = m0 + wm * (32 * A) + row;
+        const float bvl = (p.bias && ml < Mg) ? (float)__builtin_bit_cast(_Float16, p.b[g * Mg + ml]) : 0.0f;
+        if (row < 32 * A) bw[row] = bvl;
+    }
+    typedef float __attribute__((ext_vector_type(4), may_alias)) floatx4;
+    asm volatile("" ::: "memory");
+    floatx4 bv[A][4];                            // rows 32i + 8q + 4lh + (0..3)
 #pragma unroll
     for (int i = 0; i < A; ++i)
 #pragma unroll
-        for (int e = 0; e < 16; ++e) {
-            const int ml = m0 + wm * (32 * A) + i * 32 + 8 * (e >> 2) + 4 * lh + (e & 3);
-            bv[i][e] = (p.bias && ml < Mg) ? (float)__builtin_bit_cast(_Float16, p.b[g * Mg + ml]) : 0.0f;
-        }
+        for (int q = 0; q < 4; ++q) bv[i][q] = *reinterpret_cast<const floatx4 *>(bw + 32 * i + 8 * q + 4 * lh);
+    const float floor_v = p.relu ? 0.0f : -__builtin_inff();
+    u16_alias *elw = el + (4 * lh) * EP + l32;    // this lane's column of the transpose tile
+    const int row0 = lane >> 2, chunk = lane & 3;
+    const u16_alias *elr = el + row0 * EP + chunk * 8;
+    const int ml0 = m0 + wm * (32 * A) + row0;
+    uint16_t *ybase = p.y + ((size_t)n * p.M + (size_t)g * Mg + ml0) * HoWo;
+    const size_t kstride = (size_t)16 * HoWo;    // 16 rows further per read round
     const int ov = p.out_vec;                    // pixels per store: divides Wo, tile_w and the base alignment
 #pragma unroll
     for (int j = 0; j < B; ++j) {
@@ -532,47 +560,65 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void igemm_kernel(const Con
         for (int i = 0; i < A; ++i)
 #pragma unroll
             for (int e = 0; e < 16; ++e) {
-                float v = acc[i][j][e] + bv[i][e];
-                if (p.relu) v = fmaxf(v, 0.0f);
-                const int row = i * 32 + 8 * (e >> 2) + 4 * lh + (e & 3);
-                el[row * EP + l32] = __builtin_bit_cast(uint16_t, (_Float16)v);
+                const float v = fmaxf(acc[i][j][e] + bv[i][e >> 2][e & 3], floor_v);
+                elw[(i * 32 + 8 * (e >> 2) + (e & 3)) * EP] = __builtin_bit_cast(uint16_t, (_Float16)v);
+            }
+        asm volatile("" ::: "memory");          // the reads below see the writes above
+        const int pix0 = (wn * B + j) * 32 + chunk * 8;
+        if (ov == 8) {
+            const int oh = oh0 + (pix0 >> p.log2_tw), ow = ow0 + (pix0 & (TW - 1));
+            const bool ok = oh < p.Ho && ow < p.Wo;
+            uint16_t *dst = ybase + oh * p.Wo + ow;
+#pragma unroll
+            for (int k = 0; k < 2 * A; ++k) {
+                const u32x4 v = *reinterpret_cast<const u32x4_alias *>(elr + k * 16 * EP);
+                if (ok && ml0 + 16 * k < Mg) *reinterpret_cast<u32x4 *>(dst + k * kstride) = v;
+            }
+        } else if (ov == 4) {
+            bool ok[2];
+            uint16_t *dst[2];
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const int pix = pix0 + 4 * h;
+                const int oh = oh0 + (pix >> p.log2_tw), ow = ow0 + (pix & (TW - 1));
+                ok[h] = oh < p.Ho && ow < p.Wo;
+                dst[h] = ybase + oh * p.Wo + ow;
             }
 #pragma unroll
-        for (int k = 0; k < 2 * A; ++k) {
-            const int id = lane + 64 * k;
-            const int row = id >> 2, chunk = id & 3;
-            const u32x4 v = *reinterpret_cast<const u32x4 *>(el + row * EP + chunk * 8);
-            const int ml = m0 + wm * (32 * A) + row;
-            if (ml >= Mg) continue;
-            uint16_t *yrow = p.y + ((size_t)n * p.M + (size_t)g * Mg + ml) * HoWo;
-            const int pix0 = (wn * B + j) * 32 + chunk * 8;
-            if (ov == 8) {
-                const int oh = oh0 + (pix0 >> p.log2_tw), ow = ow0 + (pix0 & (TW - 1));
-                if (oh < p.Ho && ow < p.Wo) *reinterpret_cast<u32x4 *>(yrow + oh * p.Wo + ow) = v;
-            } else if (ov == 4) {
+            for (int k = 0; k < 2 * A; ++k) {
+                const u32x4 v = *reinterpret_cast<const u32x4_alias *>(elr + k * 16 * EP);
 #pragma unroll
-                for (int h = 0; h < 2; ++h) {
-                    const int pix = pix0 + 4 * h;
-                    const int oh = oh0 + (pix >> p.log2_tw), ow = ow0 + (pix & (TW - 1));
-                    if (oh < p.Ho && ow < p.Wo) {
-                        uint2 t = make_uint2(v[2 * h], v[2 * h + 1]);
-                        *reinterpret_cast<uint2 *>(yrow + oh * p.Wo + ow) = t;
-                    }
-                }
-            } else if (ov == 2) {
+                for (int h = 0; h < 2; ++h)
+                    if (ok[h] && ml0 + 16 * k < Mg)
+                        *reinterpret_cast<uint2 *>(dst[h] + k * kstride) = make_uint2(v[2 * h], v[2 * h + 1]);
+            }
+        } else if (ov == 2) {
+            bool ok[4];
+            uint16_t *dst[4];
 #pragma unroll
-                for (int h = 0; h < 4; ++h) {
-                    const int pix = pix0 + 2 * h;
-                    const int oh = oh0 + (pix >> p.log2_tw), ow = ow0 + (pix & (TW - 1));
-                    if (oh < p.Ho && ow < p.Wo) *reinterpret_cast<uint32_t *>(yrow + oh * p.Wo + ow) = v[h];
-                }
-            } else {
+            for (int h = 0; h < 4; ++h) {
+                const int pix = pix0 + 2 * h;
+                const int oh = oh0 + (pix >> p.log2_tw), ow = ow0 + (pix & (TW - 1));
+                ok[h] = oh < p.Ho && ow < p.Wo;
+                dst[h] = ybase + oh * p.Wo + ow;
+            }
+#pragma unroll
+            for (int k = 0; k < 2 * A; ++k) {
+                const u32x4 v = *reinterpret_cast<const u32x4_alias *>(elr + k * 16 * EP);
+#pragma unroll
+                for (int h = 0; h < 4; ++h)
+                    if (ok[h] && ml0 + 16 * k < Mg) *reinterpret_cast<uint32_t *>(dst[h] + k * kstride) = v[h];
+            }
+        } else {
+            for (int k = 0; k < 2 * A; ++k) {
+                const u32x4 v = *reinterpret_cast<const u32x4_alias *>(elr + k * 16 * EP);
+                if (ml0 + 16 * k >= Mg) continue;
 #pragma unroll
                 for (int h = 0; h < 8; ++h) {
                     const int pix = pix0 + h;
                     const int oh = oh0 + (pix >> p.log2_tw), ow = ow0 + (pix & (TW - 1));
                     if (oh < p.Ho && ow < p.Wo)
-                        yrow[oh * p.Wo + ow] = (uint16_t)(v[h >> 1] >> (16 * (h & 1)));
+                        (ybase + k * kstride)[oh * p.Wo + ow] = (uint16_t)(v[h >> 1] >> (16 * (h & 1)));
                 }
             }
         }
@@ -638,6 +684,13 @@ static const IgemmVariant g_variants[] = {
     HGC_VX(1, 2, 2, 1, 4, 8, 2, 1, 1, 2, 4),    // pointwise  64 ch x 256 px
     HGC_VR(1, 2, 2, 1, 4, 8, 2, 2, 4),
     HGC_VX(1, 2, 1, 1, 4, 8, 2, 1, 1, 2, 4),    // pointwise  64 ch x 128 px
+    HGC_VX(1, 2, 2, 1, 4, 8, 1, 1, 1, 2, 4),    // pointwise  64 ch x 256 px, one LDS buffer (few channel blocks)
+    HGC_VX(1, 2, 1, 1, 4, 8, 1, 1, 1, 2, 4),    // pointwise  64 ch x 128 px, one LDS buffer
+    HGC_VX(1, 2, 2, 1, 4, 4, 1, 1, 1, 2, 4),    // pointwise  64 ch x 256 px, 32 channels per step, one LDS buffer
+    HGC_VX(1, 4, 1, 1, 4, 8, 1, 1, 1, 2, 4),    // pointwise 128 ch x 128 px, one LDS buffer
+    HGC_VX(1, 2, 4, 1, 4, 8, 1, 1, 4, 4, 4),    // pointwise  64 ch x 512 px: many loads in flight per wave
+    HGC_VX(1, 2, 4, 1, 4, 4, 1, 1, 2, 4, 4),    // pointwise  64 ch x 512 px, 32 channels per step
+    HGC_VX(1, 4, 4, 1, 4, 4, 1, 1, 2, 4, 4),    // pointwise 128 ch x 512 px, 32 channels per step
     HGC_VX(5, 2, 2, 1, 4, 2, 1, 1, 2, 3, 4),    // 5x5  64 ch x 256 px
     HGC_VR(5, 2, 2, 1, 4, 2, 1, 3, 4),
     HGC_VR(7, 1, 2, 1, 4, 2, 1, 3, 6),          // stem-like 7x7: 32 ch x 256 px
