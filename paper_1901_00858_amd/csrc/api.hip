@@ -99,7 +99,7 @@ static double estimate_cycles(const Geometry &g, const Candidate &c)
 {
     const IgemmVariant &v = *c.v;
     const int T = v.ks * v.ks;
-    const int NW = v.waves_m * v.waves_n, NT = 64 * NW;
+    const int NW = v.waves_m * v.waves_n, NT = 64 * v.stage_waves();
     const int RPW = v.BM() / NW;
     const int WLR = (RPW * v.npl * T + 63) / 64, WIR = (RPW * v.npl + 63) / 64;
     const int items = v.npl * c.PH * (c.PWU / v.xvec);
@@ -121,7 +121,7 @@ static double estimate_cycles(const Geometry &g, const Candidate &c)
     const int regs = 16 * v.wm_blocks * v.wn_blocks + 90;
     const int waves_simd = std::max(1, std::min(8, 512 / regs));
     int k = (int)std::min<double>(waves_simd / std::max(1.0, w), (double)(kMaxLds / std::max<long long>(c.lds, 1)));
-    k = std::max(1, std::min(k, 2048 / NT));
+    k = std::max(1, std::min(k, 2048 / v.threads()));
     const long long wgs = c.grid * c.split;
     const long long on_cu = (wgs + 255) / 256;                          // workgroups the busiest CU gets
     k = (int)std::min<long long>(k, on_cu);
@@ -436,9 +436,10 @@ int32_t hgc_igemm_variant_name(int32_t packed, int32_t variant, char *buf, int32
     if (!buf || buf_len < 1 || variant < 0 || variant >= nv) return -1;
     const IgemmVariant &v = vs[variant];
     // the kernel's template arguments, in order, as rocprofv3 prints them (without the split flag)
-    return (int32_t)snprintf(buf, (size_t)buf_len, "igemm_kernel<%d, %d, %d, %d, %d, %d, %d, %s, %s, %d, %d",
+    return (int32_t)snprintf(buf, (size_t)buf_len, "igemm_kernel<%d, %d, %d, %d, %d, %d, %d, %s, %s, %d, %d, %d",
                              v.ks, v.wm_blocks, v.wn_blocks, v.waves_m, v.waves_n, v.npl, v.xvec,
-                             v.calign ? "true" : "false", v.packed ? "true" : "false", v.nstage, v.max_rounds);
+                             v.calign ? "true" : "false", v.packed ? "true" : "false", v.nstage, v.max_rounds,
+                             v.prod_waves);
 }
 
 const char *hgc_last_launch_error(void)

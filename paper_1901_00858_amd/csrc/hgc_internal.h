@@ -48,9 +48,9 @@ struct ConvArgs {
 
 // LDS units (16 bytes) of one weight buffer: every wave owns a slice that holds
 // its BM/NW rows, rounded up so that each lane of each 64-lane load round lands inside.
-constexpr int igemm_w_units(int ks, int wm_blocks, int waves_m, int waves_n, int npl)
+constexpr int igemm_w_units(int ks, int wm_blocks, int waves_m, int stage_waves, int npl)
 {
-    const int nw = waves_m * waves_n;
+    const int nw = stage_waves;
     const int rpw = 32 * wm_blocks * waves_m / nw;
     const int wch = rpw * npl * ks * ks;
     return nw * ((wch + 63) / 64) * 64;
@@ -67,18 +67,22 @@ struct IgemmVariant {
     int xvec;            // pixels per global load of the input (1 or 2)
     int calign;          // 1: Cg % 8 == 0, weights fetched as 16-byte vectors
     int packed;          // 1: weights in the pre-packed layout
-    int nstage;          // LDS buffers (2 = double buffered)
+    int nstage;          // LDS buffers (2 = double buffered; 3 = loads two steps ahead)
     int max_rounds;      // patch staging rounds pipelined through registers
+    int prod_waves;      // waves that only stage operands (0: every wave stages and runs MFMAs)
     hipError_t (*launch)(const ConvArgs &, size_t lds_bytes, hipStream_t stream);
     int BM() const { return 32 * wm_blocks * waves_m; }
     int BN() const { return 32 * wn_blocks * waves_n; }
-    int threads() const { return 64 * waves_m * waves_n; }
+    int threads() const { return 64 * (waves_m * waves_n + prod_waves); }
+    int stage_waves() const { return prod_waves ? prod_waves : waves_m * waves_n; }
     // LDS of a launch: stages of {weights, patch + 8 dump units}; the epilogue reuses it
     long long lds_bytes(int PH, int PWU) const
     {
-        const long long stage = 16LL * (igemm_w_units(ks, wm_blocks, waves_m, waves_n, npl) + npl * PH * PWU + 8);
+        const long long wu = igemm_w_units(ks, wm_blocks, waves_m, stage_waves(), npl), xu = npl * PH * PWU + 8;
+        // nstage 3: three weight buffers, two patch buffers (the patch waits in registers one step longer)
+        const long long main = 16LL * (nstage == 3 ? 3 * wu + 2 * xu : nstage * (wu + xu));
         const long long epi = 84LL * 32 * wm_blocks * waves_m * waves_n;   // transpose tile + bias per wave
-        return nstage * stage > epi ? nstage * stage : epi;
+        return main > epi ? main : epi;
     }
 };
 

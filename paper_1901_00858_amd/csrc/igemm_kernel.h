@@ -38,6 +38,7 @@
 // before the MFMAs of step s and are stored to the other buffer after them.
 #pragma once
 #include <atomic>
+#include <type_traits>
 
 #include "hgc_internal.h"
 
@@ -62,6 +63,15 @@ __device__ __forceinline__ uint32_t pack_lo(uint32_t a, uint32_t b)   // a.lo | 
 __device__ __forceinline__ uint32_t pack_hi(uint32_t a, uint32_t b)   // a.hi | b.hi << 16
 {
     return __builtin_amdgcn_perm(b, a, 0x07060302u);
+}
+
+// Workgroup barrier for data exchanged through LDS only.  __syncthreads() also waits
+// for every outstanding vector-memory operation (vmcnt(0)), which would drain the loads
+// that are deliberately left in flight across K steps; LDS operations are counted by
+// lgkmcnt alone, and LDS-direct loads are waited for explicitly where they are consumed.
+__device__ __forceinline__ void lds_barrier()
+{
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
 }
 
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void *base, uint32_t bytes)
@@ -102,27 +112,32 @@ typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 // XVEC pixels (XVEC*2 bytes) of each of the 8 channels of the item's plane.
 // d[j][k]: channel j, dword k (two pixels per dword; one pixel when XVEC == 1).
 template <int XVEC, bool CALIGN>
+__device__ __forceinline__ void load_patch_chan(__amdgpu_buffer_rsrc_t rx, const PatchItem &it, int c0,
+                                                int Cg, uint32_t soff, uint32_t chan_bytes, int j,
+                                                uint32_t (&dj)[(XVEC + 1) / 2])
+{
+    const uint32_t vo = (c0 + it.pl8 + (CALIGN ? 0 : j) < Cg) ? it.voff : kNoLoad;
+    const uint32_t so = soff + j * chan_bytes;
+    if (XVEC == 8) {
+        const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rx, vo, so, 0);
+        dj[0] = v.x; dj[1 % ((XVEC + 1) / 2)] = v.y; dj[2 % ((XVEC + 1) / 2)] = v.z; dj[3 % ((XVEC + 1) / 2)] = v.w;
+    } else if (XVEC == 4) {
+        const u32x2 v = __builtin_amdgcn_raw_buffer_load_b64(rx, vo, so, 0);
+        dj[0] = v.x; dj[1 % ((XVEC + 1) / 2)] = v.y;
+    } else if (XVEC == 2) {
+        dj[0] = __builtin_amdgcn_raw_buffer_load_b32(rx, vo, so, 0);
+    } else {
+        dj[0] = (uint16_t)__builtin_amdgcn_raw_buffer_load_b16(rx, vo, so, 0);
+    }
+}
+
+template <int XVEC, bool CALIGN>
 __device__ __forceinline__ void load_patch_item(__amdgpu_buffer_rsrc_t rx, const PatchItem &it, int c0,
                                                 int Cg, uint32_t soff, uint32_t chan_bytes,
                                                 uint32_t (&d)[8][(XVEC + 1) / 2])
 {
-    const uint32_t vplane = (c0 + it.pl8 < Cg) ? it.voff : kNoLoad;
 #pragma unroll
-    for (int j = 0; j < 8; ++j) {
-        const uint32_t vo = CALIGN ? vplane : ((c0 + it.pl8 + j < Cg) ? it.voff : kNoLoad);
-        const uint32_t so = soff + j * chan_bytes;
-        if (XVEC == 8) {
-            const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rx, vo, so, 0);
-            d[j][0] = v.x; d[j][1 % ((XVEC + 1) / 2)] = v.y; d[j][2 % ((XVEC + 1) / 2)] = v.z; d[j][3 % ((XVEC + 1) / 2)] = v.w;
-        } else if (XVEC == 4) {
-            const u32x2 v = __builtin_amdgcn_raw_buffer_load_b64(rx, vo, so, 0);
-            d[j][0] = v.x; d[j][1 % ((XVEC + 1) / 2)] = v.y;
-        } else if (XVEC == 2) {
-            d[j][0] = __builtin_amdgcn_raw_buffer_load_b32(rx, vo, so, 0);
-        } else {
-            d[j][0] = (uint16_t)__builtin_amdgcn_raw_buffer_load_b16(rx, vo, so, 0);
-        }
-    }
+    for (int j = 0; j < 8; ++j) load_patch_chan<XVEC, CALIGN>(rx, it, c0, Cg, soff, chan_bytes, j, d[j]);
 }
 
 // Transpose 8 channels x XVEC pixels into XVEC units of 8 channels.
@@ -164,30 +179,31 @@ __device__ __forceinline__ void interleave_hint()
 // step.  XVEC: input pixels per global load (1, 2, 4 or 8; W and the byte alignment
 // of x must be multiples of it).  CALIGN: Cg % 8 == 0 and a 16-byte aligned weight base.
 // PACKED: weights come from the pre-packed layout (see pack.hip) and need no regrouping.
-// NSTAGE: LDS buffers (1 or 2).  MAXR: patch staging rounds held in registers.  SPLITK: write
+// NSTAGE: LDS buffers (1, 2, or 3 = three weight and two patch buffers with the loads two steps ahead).  MAXR: patch staging rounds held in registers.  SPLITK: write
 // FP32 partial sums of a slice of the channel blocks instead of the output.
 template <int KS, int A, int B, int WAVES_M, int WAVES_N, int NPL, int XVEC, bool CALIGN, bool PACKED,
-          int NSTAGE, int MAXR, bool SPLITK>
-__global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void igemm_kernel(const ConvArgs p)
+          int NSTAGE, int MAXR, int PW, bool SPLITK>
+__global__ __launch_bounds__(64 * (WAVES_M * WAVES_N + PW)) void igemm_kernel(const ConvArgs p)
 {
-    constexpr int NW = WAVES_M * WAVES_N;
-    constexpr int NT = 64 * NW;
+    constexpr int NW = WAVES_M * WAVES_N;        // waves that run the MFMAs
+    constexpr int NWS = PW ? PW : NW;            // waves that stage the operands
+    constexpr int NT = 64 * NWS;                 // staging threads
     constexpr int BM = 32 * A * WAVES_M;
     constexpr int BN = 32 * B * WAVES_N;
     constexpr int T = KS * KS;
     constexpr int CB = 8 * NPL;
-    constexpr int RPW = BM / NW;                 // weight rows staged by one wave
+    constexpr int RPW = BM / NWS;                // weight rows staged by one wave
     constexpr int CPR = NPL * T;                 // 16-byte chunks per row per step
     constexpr int WCH = RPW * CPR;               // chunks (= LDS units) of one wave's rows
     constexpr int WLR = (WCH + 63) / 64;         // LDS-direct load rounds per lane
     constexpr int WSL = WLR * 64;                // LDS units of one wave's slice (every lane of every round lands inside)
-    constexpr int W_UNITS = NW * WSL;
+    constexpr int W_UNITS = NWS * WSL;
     constexpr int WIT = RPW * NPL;               // (row, plane) items per wave
     constexpr int WIR = (WIT + 63) / 64;
     constexpr int TC = T < 9 ? T : 9;            // taps handled together by the scalar weight path
     static_assert(NPL % 2 == 0, "planes come in pairs (16 channels per MFMA)");
-    static_assert(BM % NW == 0 && (RPW & (RPW - 1)) == 0, "rows per wave must be a power of two");
-    static_assert(W_UNITS == igemm_w_units(KS, A, WAVES_M, WAVES_N, NPL), "host and kernel disagree on LDS");
+    static_assert(BM % NWS == 0 && (RPW & (RPW - 1)) == 0, "rows per wave must be a power of two");
+    static_assert(W_UNITS == igemm_w_units(KS, A, WAVES_M, NWS, NPL), "host and kernel disagree on LDS");
 
     extern __shared__ u32x4 lds[];
     const int X_UNITS = NPL * p.PH * p.PWU + 8;  // + dump units (one item's worth) for staging items past the end
@@ -197,6 +213,10 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void igemm_kernel(const Con
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    // with PW > 0 waves NW .. NW+PW-1 only stage (producers) and waves 0 .. NW-1 only
+    // run MFMAs (consumers); otherwise every wave does both
+    const int sw = PW ? wave - NW : wave;        // staging wave index (negative: not a staging wave)
+    const int stid = PW ? tid - 64 * NW : tid;   // staging thread index
     const int wm = wave % WAVES_M;
     const int wn = wave / WAVES_M;
     const int l32 = lane & 31;
@@ -243,24 +263,25 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void igemm_kernel(const Con
     PatchItem pit[MAXR];
 #pragma unroll
     for (int r = 0; r < MAXR; ++r)
-        pit[r] = decode_patch_item<XVEC>(r * NT + tid, total_items, ipr, PH, PWU, ih0, iwa, p.H, p.W, HW,
-                                         plane0_off, dump_unit);
-    uint32_t xreg[MAXR][8][(XVEC + 1) / 2];
+        pit[r] = decode_patch_item<XVEC>(r * NT + (stid < 0 ? 0 : stid), total_items, ipr, PH, PWU, ih0, iwa,
+                                         p.H, p.W, HW, plane0_off, dump_unit);
+    typedef uint32_t XRegs[MAXR][8][(XVEC + 1) / 2];
+    XRegs xreg[NSTAGE == 3 ? 2 : 1];             // NSTAGE 3: two steps of loads in flight
 
-    auto load_x = [&](int st) {
+    auto load_x = [&](int st, XRegs &xr) {
         const uint32_t soff = (uint32_t)(st * CB) * chan_bytes;
 #pragma unroll
         for (int r = 0; r < MAXR; ++r)
-            load_patch_item<XVEC, CALIGN>(rx, pit[r], st * CB, Cg, soff, chan_bytes, xreg[r]);
+            load_patch_item<XVEC, CALIGN>(rx, pit[r], st * CB, Cg, soff, chan_bytes, xr[r]);
     };
-    auto store_x = [&](int st, u32x4 *xl) {
+    auto store_x = [&](int st, u32x4 *xl, const XRegs &xr) {
 #pragma unroll
-        for (int r = 0; r < MAXR; ++r) store_patch_item<XVEC>(xl, pit[r], xreg[r]);
+        for (int r = 0; r < MAXR; ++r) store_patch_item<XVEC>(xl, pit[r], xr[r]);
         // patches larger than the register capacity: remaining rounds, not pipelined
         if (rounds > MAXR) {
             const uint32_t soff = (uint32_t)(st * CB) * chan_bytes;
             for (int r = MAXR; r < rounds; ++r) {
-                PatchItem it = decode_patch_item<XVEC>(r * NT + tid, total_items, ipr, PH, PWU, ih0, iwa,
+                PatchItem it = decode_patch_item<XVEC>(r * NT + stid, total_items, ipr, PH, PWU, ih0, iwa,
                                                        p.H, p.W, HW, plane0_off, dump_unit);
                 uint32_t d[8][(XVEC + 1) / 2];
                 load_patch_item<XVEC, CALIGN>(rx, it, st * CB, Cg, soff, chan_bytes, d);
@@ -281,7 +302,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void igemm_kernel(const Con
         for (int k = 0; k < WLR; ++k) {
             const int u = lane + 64 * k;
             const int t = u / (NPL * RPW), pl = (u / RPW) % NPL, r = u % RPW;
-            const int m = m0 + wave * RPW + r;
+            const int m = m0 + sw * RPW + r;
             const bool ok = (u < WCH) && (m < p.MB8 * 8);
             wvoff[k] = ok ? p.wp_off + 16u * (uint32_t)((((g * p.MB8 + (m >> 3)) * p.NP8 + pl) * T + t) * 8 + (m & 7))
                           : p.wp_zero;
@@ -292,35 +313,34 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void igemm_kernel(const Con
         for (int k = 0; k < WLR; ++k) {
             const int id = lane + 64 * k;
             const int row = id / CPR, j = id % CPR;
-            const int m = m0 + wave * RPW + row;
+            const int m = m0 + sw * RPW + row;
             wvoff[k] = (id < WCH && m < Mg) ? wgrp_off + 2u * (uint32_t)(m * Cg * T + j * 8) : kNoLoad;
             wpl8[k] = (j / T) * 8;
         }
     }
-    auto load_w = [&](int st, u32x4 *wl) {
-        if (!WDMA) return;
-        u32x4 *mine = wl + wave * WSL;
+    // LDS-direct load round k of step st into this wave's slice of the weight buffer wl
+    auto load_w_round = [&](int st, u32x4 *wl, int k) {
+        u32x4 *mine = wl + sw * WSL;
         if (PACKED) {
             const uint32_t soff = 16u * (uint32_t)(st * NPL * T * 8);
-#pragma unroll
-            for (int k = 0; k < WLR; ++k) {
-                // planes past the last channel: read the zero page (the scalar offset must not move it)
-                const bool inside = (wvoff[k] != p.wp_zero) && (st * NPL + wpl8[k] < p.NP8);
-                const uint32_t vo = inside ? wvoff[k] : p.wp_zero - soff;
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(rw, (lds_ptr_t)(mine + 64 * k), 16, vo, soff, 0, 0);
-            }
+            // planes past the last channel: read the zero page (the scalar offset must not move it)
+            const bool inside = (wvoff[k] != p.wp_zero) && (st * NPL + wpl8[k] < p.NP8);
+            const uint32_t vo = inside ? wvoff[k] : p.wp_zero - soff;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rw, (lds_ptr_t)(mine + 64 * k), 16, vo, soff, 0, 0);
         } else {
             const uint32_t soff = 2u * (uint32_t)(st * CB * T);
-#pragma unroll
-            for (int k = 0; k < WLR; ++k) {
-                const uint32_t vo = (st * CB + wpl8[k] < Cg) ? wvoff[k] : kNoLoad;
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(rw, (lds_ptr_t)(mine + 64 * k), 16, vo, soff, 0, 0);
-            }
+            const uint32_t vo = (st * CB + wpl8[k] < Cg) ? wvoff[k] : kNoLoad;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rw, (lds_ptr_t)(mine + 64 * k), 16, vo, soff, 0, 0);
         }
+    };
+    auto load_w = [&](int st, u32x4 *wl) {
+        if (!WDMA) return;
+#pragma unroll
+        for (int k = 0; k < WLR; ++k) load_w_round(st, wl, k);
     };
     // regroup items: lanes past the item count redo item (lane % WIT) and write the dump unit
     auto store_w = [&](int st, u32x4 *wl, u32x4 *xl) {
-        u32x4 *mine = wl + wave * WSL;           // this wave's slice: final layout [T][NPL][RPW]
+        u32x4 *mine = wl + sw * WSL;             // this wave's slice: final layout [T][NPL][RPW]
         if (PACKED) return;                      // already in the final layout
         if (CALIGN) {
             // the raw rows ([row][CPR] chunks) have landed (caller waited on vmcnt);
@@ -339,7 +359,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void igemm_kernel(const Con
                 const bool real = (WIT % 64 == 0) || (lane + 64 * k < WIT);
                 const int item = (lane + 64 * k) % WIT;
                 const int row = item % RPW, pl = item / RPW;
-                const bool ok = (m0 + wave * RPW + row < Mg) && (st * CB + pl * 8 < Cg);
+                const bool ok = (m0 + sw * RPW + row < Mg) && (st * CB + pl * 8 < Cg);
                 u32x4 *dst = real ? mine + pl * RPW + row : xl + dump_unit;
                 const int tstride = real ? NPL * RPW : 0;
 #pragma unroll
@@ -365,7 +385,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void igemm_kernel(const Con
                 const bool real = (WIT % 64 == 0) || (lane + 64 * k < WIT);
                 const int item = (lane + 64 * k) % WIT;
                 const int row = item % RPW, pl = item / RPW;
-                const int m = m0 + wave * RPW + row;
+                const int m = m0 + sw * RPW + row;
                 const int c0 = st * CB + pl * 8;
                 const uint32_t vrow = (real && m < Mg) ? wgrp_off + 2u * (uint32_t)((m * Cg + c0) * T) : kNoLoad;
                 u32x4 *dst = real ? mine + pl * RPW + row : xl + dump_unit;
@@ -415,11 +435,15 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void igemm_kernel(const Con
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
 
-    // One K step: T taps x NPL/2 plane pairs.  Fragments are double-buffered in
-    // registers: the ds_reads of iteration it+1 are issued before the MFMAs of
-    // iteration it, so their latency hides behind A*B MFMAs.
+    // One K step: T taps x NPL/2 plane pairs, walked in two halves.  An iteration of a
+    // large tile (A*B >= 4 MFMAs) hides the latency of the next iteration's ds_reads, so
+    // its fragments are double-buffered in registers.  An iteration of a small tile is one
+    // or two MFMAs, far shorter than a ds_read_b128: there all fragments of a half are
+    // read in one burst (BURST) and the MFMAs follow as the reads return in order.
+    constexpr int NIT_ALL = T * (NPL / 2);
+    constexpr int NIT_H = (NIT_ALL + 1) / 2;
+    constexpr bool BURST = (A * B <= 2) && (NIT_H * (A + B) <= 27);
     auto compute = [&](const u32x4 *wl, const u32x4 *xl, int it0, int it1) {
-        constexpr int NIT = T * (NPL / 2);
         half8 af[2][A], bf[2][B];
         auto frag_load = [&](int it, half8 (&fa)[A], half8 (&fb)[B]) {
             const int t = it / (NPL / 2), pp = it % (NPL / 2);
@@ -433,7 +457,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void igemm_kernel(const Con
         };
         frag_load(it0, af[it0 & 1], bf[it0 & 1]);
 #pragma unroll
-        for (int it = 0; it < NIT; ++it) {
+        for (int it = 0; it < NIT_ALL; ++it) {
             if (it < it0 || it >= it1) continue;
             if (it + 1 < it1) frag_load(it + 1, af[(it + 1) & 1], bf[(it + 1) & 1]);
 #pragma unroll
@@ -444,8 +468,57 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void igemm_kernel(const Con
                                                                        acc[i][j], 0, 0, 0);
         }
     };
-    constexpr int NIT_ALL = T * (NPL / 2);
-    constexpr int NIT_H = (NIT_ALL + 1) / 2;
+    // The small-tile step.  The texture-address unit of a CU accepts one wave-wide
+    // vector-memory instruction every ~16 cycles and the issuing wave waits for it; with one
+    // wave per SIMD nothing else would run meanwhile.  So the loads of a later step (LOADS:
+    // 0 none, 1 the patch, 2 patch and weights; step stn into registers xr and weight buffer
+    // wnext) are issued one or two at a time behind each MFMA, with scheduling fences
+    // that keep them there.
+    constexpr int NLD_X = 8 * MAXR, NLD_W = WDMA ? WLR : 0;
+    auto burst_step = [&](const u32x4 *wl, const u32x4 *xl, auto loads, int stn, u32x4 *wnext, XRegs &xr) {
+        constexpr int LOADS = decltype(loads)::value;
+        constexpr int NM = NIT_ALL * A * B;
+        constexpr int NLD = LOADS == 0 ? 0 : (LOADS == 1 ? NLD_X : NLD_X + NLD_W);
+        const uint32_t xsoff = (uint32_t)(stn * CB) * chan_bytes;
+        half8 af[NIT_H][A], bf[NIT_H][B];
+#pragma unroll
+        for (int h0 = 0; h0 < NIT_ALL; h0 += NIT_H) {
+#pragma unroll
+            for (int it = h0; it < h0 + NIT_H && it < NIT_ALL; ++it) {
+                const int t = it / (NPL / 2), pp = it % (NPL / 2);
+                const int toff = (t / KS) * PWU + (t % KS) + pp * plane_pair_stride;
+#pragma unroll
+                for (int i = 0; i < A; ++i)
+                    af[it - h0][i] = __builtin_bit_cast(half8, wl[ab[i] + (t * NPL + pp * 2) * RPW]);
+#pragma unroll
+                for (int j = 0; j < B; ++j) bf[it - h0][j] = __builtin_bit_cast(half8, xl[xb[j] + toff]);
+            }
+            __builtin_amdgcn_sched_barrier(0);       // the reads of the half stay ahead of its MFMAs
+#pragma unroll
+            for (int it = h0; it < h0 + NIT_H && it < NIT_ALL; ++it)
+#pragma unroll
+                for (int i = 0; i < A; ++i)
+#pragma unroll
+                    for (int j = 0; j < B; ++j) {
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af[it - h0][i], bf[it - h0][j],
+                                                                           acc[i][j], 0, 0, 0);
+                        const int m = (it * A + i) * B + j;
+#pragma unroll
+                        for (int slot = m * NLD / NM; slot < (m + 1) * NLD / NM; ++slot) {
+                            if (slot < NLD_X)
+                                load_patch_chan<XVEC, CALIGN>(rx, pit[slot / 8], stn * CB, Cg, xsoff, chan_bytes,
+                                                              slot % 8, xr[slot / 8][slot % 8]);
+                            else
+                                load_w_round(stn, wnext, slot - NLD_X);
+                        }
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+        }
+    };
+    typedef std::integral_constant<int, 0> no_loads;
+    typedef std::integral_constant<int, 1> patch_loads;
+    typedef std::integral_constant<int, 2> all_loads;
+
     // ---- K loop over channel blocks ----
     int st0 = 0, st1 = p.nsteps;
     if (SPLITK) {
@@ -454,46 +527,169 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void igemm_kernel(const Con
     }
     // all outstanding vector-memory operations (patch loads and LDS-direct weight rows)
     auto wait_vmem = [&]() { __builtin_amdgcn_s_waitcnt(0x0F70); };
-    if (NSTAGE == 2) {
-        load_x(st0);
+    if constexpr (PW > 0) {
+        // Producer and consumer waves.  A wave that issues vector-memory instructions waits
+        // on the CU's address unit and a wave that transposes and stores is not issuing
+        // MFMAs; with one wave per SIMD these phases would add up.  Here PW waves only
+        // stage (loads two steps ahead, three weight buffers, two patch buffers) and the
+        // other waves only read fragments and issue MFMAs; both meet at one barrier per step.
+        static_assert(PW == 0 || (NSTAGE == 3 && BURST && WDMA), "specialised waves use the two-steps-ahead pipeline");
+        constexpr int NLD = 8 * MAXR + WLR;
+        static_assert(NLD < 64, "vmcnt is a 6-bit counter");
+        constexpr int WAIT_OLDER = (NLD & 15) | ((NLD >> 4) << 14) | 0x0F70;
+        u32x4 *const xbuf0 = lds + 3 * W_UNITS;
+        if (wave >= NW) {
+            auto stage_step = [&](int st, int wi, auto parity) {
+                constexpr int P = decltype(parity)::value;
+                const bool has1 = st + 1 < st1, has2 = st + 2 < st1;
+                const int w1 = wi == 2 ? 0 : wi + 1, w2 = w1 == 2 ? 0 : w1 + 1;
+                if (has2) {
+                    load_x(st + 2, xreg[P]);
+                    load_w(st + 2, lds + w2 * W_UNITS);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+                if (has1) {
+                    if (has2) __builtin_amdgcn_s_waitcnt(WAIT_OLDER); else wait_vmem();
+                    u32x4 *xn_ = xbuf0 + (P ^ 1) * X_UNITS;
+                    store_x(st + 1, xn_, xreg[P ^ 1]);
+                    store_w(st + 1, lds + w1 * W_UNITS, xn_);
+                }
+                lds_barrier();
+            };
+            load_x(st0, xreg[0]);
+            load_w(st0, lds);
+            if (st0 + 1 < st1) {
+                load_x(st0 + 1, xreg[1]);
+                load_w(st0 + 1, lds + W_UNITS);
+                __builtin_amdgcn_sched_barrier(0);
+                __builtin_amdgcn_s_waitcnt(WAIT_OLDER);
+            } else {
+                wait_vmem();
+            }
+            store_x(st0, xbuf0, xreg[0]);
+            store_w(st0, lds, xbuf0);
+            lds_barrier();
+            int wi = 0;
+            for (int st = st0; st < st1; st += 2) {
+                stage_step(st, wi, std::integral_constant<int, 0>());
+                wi = wi == 2 ? 0 : wi + 1;
+                if (st + 1 < st1) {
+                    stage_step(st + 1, wi, std::integral_constant<int, 1>());
+                    wi = wi == 2 ? 0 : wi + 1;
+                }
+            }
+            return;                               // the epilogue belongs to the consumers
+        }
+        lds_barrier();                          // the first step is staged
+        int wi = 0, par = 0;
+        for (int st = st0; st < st1; ++st) {
+            burst_step(lds + wi * W_UNITS, xbuf0 + par * X_UNITS, no_loads(), 0, lds, xreg[0]);
+            lds_barrier();                      // step st is consumed, step st + 1 is staged
+            wi = wi == 2 ? 0 : wi + 1;
+            par ^= 1;
+        }
+    } else if constexpr (NSTAGE == 3) {
+        // Three weight buffers and two patch buffers in LDS, two register sets for the patch:
+        // the loads of step s+2 are issued before the MFMAs of step s, so a load has a whole
+        // step to arrive.  Vector-memory loads complete in order: waiting until only the
+        // newest batch (NLD instructions) is outstanding means the older batch has landed.
+        static_assert(NSTAGE != 3 || (BURST && WDMA), "prefetch distance 2 is for the small tiles");
+        constexpr int NLD = 8 * MAXR + WLR;      // vector-memory instructions of one step's loads
+        static_assert(NLD < 64, "vmcnt is a 6-bit counter");
+        constexpr int WAIT_OLDER = (NLD & 15) | ((NLD >> 4) << 14) | 0x0F70;
+        u32x4 *const xbuf0 = lds + 3 * W_UNITS;
+        auto step = [&](int st, int wi, auto parity) {
+            constexpr int P = decltype(parity)::value;
+            const bool has1 = st + 1 < st1, has2 = st + 2 < st1;
+            u32x4 *wl = lds + wi * W_UNITS, *xl = xbuf0 + P * X_UNITS;
+            const int w1 = wi == 2 ? 0 : wi + 1, w2 = w1 == 2 ? 0 : w1 + 1;
+            if (has2) burst_step(wl, xl, all_loads(), st + 2, lds + w2 * W_UNITS, xreg[P]);
+            else burst_step(wl, xl, no_loads(), 0, lds, xreg[P]);
+            if (has1) {
+                if (has2) __builtin_amdgcn_s_waitcnt(WAIT_OLDER); else wait_vmem();
+                u32x4 *xn_ = xbuf0 + (P ^ 1) * X_UNITS;
+                store_x(st + 1, xn_, xreg[P ^ 1]);
+                store_w(st + 1, lds + w1 * W_UNITS, xn_);
+            }
+            lds_barrier();
+        };
+        load_x(st0, xreg[0]);
+        load_w(st0, lds);
+        if (st0 + 1 < st1) {
+            load_x(st0 + 1, xreg[1]);
+            load_w(st0 + 1, lds + W_UNITS);
+            __builtin_amdgcn_sched_barrier(0);
+            __builtin_amdgcn_s_waitcnt(WAIT_OLDER);
+        } else {
+            wait_vmem();
+        }
+        store_x(st0, xbuf0, xreg[0]);
+        store_w(st0, lds, xbuf0);
+        lds_barrier();
+        int wi = 0;
+        for (int st = st0; st < st1; st += 2) {
+            step(st, wi, std::integral_constant<int, 0>());
+            wi = wi == 2 ? 0 : wi + 1;
+            if (st + 1 < st1) {
+                step(st + 1, wi, std::integral_constant<int, 1>());
+                wi = wi == 2 ? 0 : wi + 1;
+            }
+        }
+    } else if constexpr (NSTAGE == 2) {
+        load_x(st0, xreg[0]);
         load_w(st0, lds);
         wait_vmem();
-        store_x(st0, lds + W_UNITS);
+        store_x(st0, lds + W_UNITS, xreg[0]);
         store_w(st0, lds, lds + W_UNITS);
-        __syncthreads();
+        lds_barrier();
         int cur = 0;
         for (int st = st0; st + 1 < st1; ++st, cur ^= 1) {
             u32x4 *wl = lds + cur * stage_units, *xl = wl + W_UNITS;
             u32x4 *wn_ = lds + (cur ^ 1) * stage_units, *xn_ = wn_ + W_UNITS;
-            // region 1: the next step's loads are issued between the first half of the MFMAs
-            load_x(st + 1);
-            load_w(st + 1, wn_);
-            compute(wl, xl, 0, NIT_H);
-            interleave_hint<NIT_H * A * B, 1, 1, 2>();
-            wait_vmem();
-            // region 2: transposes, regroup and LDS stores between the second half
-            store_x(st + 1, xn_);
-            store_w(st + 1, wn_, xn_);
-            compute(wl, xl, NIT_H, NIT_ALL);
-            interleave_hint<(NIT_ALL - NIT_H) * A * B, 0, 2, 3>();
-            __syncthreads();
+            if constexpr (BURST) {
+                burst_step(wl, xl, all_loads(), st + 1, wn_, xreg[0]);
+                wait_vmem();
+                store_x(st + 1, xn_, xreg[0]);
+                store_w(st + 1, wn_, xn_);
+            } else {
+                // region 1: the next step's loads are issued between the first half of the MFMAs
+                load_x(st + 1, xreg[0]);
+                load_w(st + 1, wn_);
+                compute(wl, xl, 0, NIT_H);
+                interleave_hint<NIT_H * A * B, 1, 1, 2>();
+                wait_vmem();
+                // region 2: transposes, regroup and LDS stores between the second half
+                store_x(st + 1, xn_, xreg[0]);
+                store_w(st + 1, wn_, xn_);
+                compute(wl, xl, NIT_H, NIT_ALL);
+                interleave_hint<(NIT_ALL - NIT_H) * A * B, 0, 2, 3>();
+            }
+            lds_barrier();
         }
-        compute(lds + cur * stage_units, lds + cur * stage_units + W_UNITS, 0, NIT_ALL);
-        __syncthreads();                          // the buffers are reused by the epilogue
+        if constexpr (BURST)
+            burst_step(lds + cur * stage_units, lds + cur * stage_units + W_UNITS, no_loads(), 0, lds, xreg[0]);
+        else
+            compute(lds + cur * stage_units, lds + cur * stage_units + W_UNITS, 0, NIT_ALL);
+        lds_barrier();                          // the buffers are reused by the epilogue
     } else {
         u32x4 *wl = lds, *xl = lds + W_UNITS;
-        load_x(st0);
+        load_x(st0, xreg[0]);
         for (int st = st0; st < st1; ++st) {
-            __syncthreads();                      // everyone is done reading the buffers
+            lds_barrier();                      // everyone is done reading the buffers
             load_w(st, wl);
             wait_vmem();
-            store_x(st, xl);
+            store_x(st, xl, xreg[0]);
             store_w(st, wl, xl);
-            __syncthreads();
-            if (st + 1 < st1) load_x(st + 1);
-            compute(wl, xl, 0, NIT_ALL);
+            lds_barrier();
+            if constexpr (BURST) {
+                if (st + 1 < st1) burst_step(wl, xl, patch_loads(), st + 1, lds, xreg[0]);
+                else burst_step(wl, xl, no_loads(), 0, lds, xreg[0]);
+            } else {
+                if (st + 1 < st1) load_x(st + 1, xreg[0]);
+                compute(wl, xl, 0, NIT_ALL);
+            }
         }
-        __syncthreads();
+        lds_barrier();
     }
 
     // ---- epilogue: accumulator register e of lane (l32, lh) in block (i, j) is
@@ -637,28 +833,34 @@ static hipError_t ensure_lds(Kern kern, size_t lds, std::atomic<size_t> &granted
     return e;
 }
 
-template <int KS, int A, int B, int WM, int WN, int NPL, int XVEC, bool CALIGN, bool PACKED, int NSTAGE, int MAXR>
+template <int KS, int A, int B, int WM, int WN, int NPL, int XVEC, bool CALIGN, bool PACKED, int NSTAGE, int MAXR,
+          int PW>
 static hipError_t launch_igemm(const ConvArgs &a, size_t lds, hipStream_t stream)
 {
-    const dim3 grid((unsigned)(((a.grid_blocks + 7) / 8) * 8)), block(64 * WM * WN);
+    const dim3 grid((unsigned)(((a.grid_blocks + 7) / 8) * 8)), block(64 * (WM * WN + PW));
     hipError_t e;
     if (a.split_k > 1) {
         static std::atomic<size_t> granted{0};
-        auto kern = igemm_kernel<KS, A, B, WM, WN, NPL, XVEC, CALIGN, PACKED, NSTAGE, MAXR, true>;
+        auto kern = igemm_kernel<KS, A, B, WM, WN, NPL, XVEC, CALIGN, PACKED, NSTAGE, MAXR, PW, true>;
         if ((e = ensure_lds(kern, lds, granted)) != hipSuccess) return e;
         hipLaunchKernelGGL(kern, grid, block, lds, stream, a);
     } else {
         static std::atomic<size_t> granted{0};
-        auto kern = igemm_kernel<KS, A, B, WM, WN, NPL, XVEC, CALIGN, PACKED, NSTAGE, MAXR, false>;
+        auto kern = igemm_kernel<KS, A, B, WM, WN, NPL, XVEC, CALIGN, PACKED, NSTAGE, MAXR, PW, false>;
         if ((e = ensure_lds(kern, lds, granted)) != hipSuccess) return e;
         hipLaunchKernelGGL(kern, grid, block, lds, stream, a);
     }
     return hipGetLastError();
 }
 
-#define HGC_V1(KS, A, B, WM, WN, NPL, XVEC, CAL, NST, MAXR)                                     \
-    {KS, A, B, WM, WN, NPL, XVEC, CAL, HGC_IGEMM_PACKED, NST, MAXR,                             \
-     &launch_igemm<KS, A, B, WM, WN, NPL, XVEC, (CAL != 0), (HGC_IGEMM_PACKED != 0), NST, MAXR>}
+#define HGC_VP(KS, A, B, WM, WN, NPL, XVEC, CAL, NST, MAXR, PW)                                 \
+    {KS, A, B, WM, WN, NPL, XVEC, CAL, HGC_IGEMM_PACKED, NST, MAXR, PW,                         \
+     &launch_igemm<KS, A, B, WM, WN, NPL, XVEC, (CAL != 0), (HGC_IGEMM_PACKED != 0), NST, MAXR, PW>}
+#define HGC_V1(KS, A, B, WM, WN, NPL, XVEC, CAL, NST, MAXR) HGC_VP(KS, A, B, WM, WN, NPL, XVEC, CAL, NST, MAXR, 0)
+// aligned-channel forms with PW producer waves (the two-steps-ahead pipeline)
+#define HGC_VS(KS, A, B, WM, WN, NPL, PW, R4, R2, R1)                                           \
+    HGC_VP(KS, A, B, WM, WN, NPL, 4, 1, 3, R4, PW),                                             \
+    HGC_VP(KS, A, B, WM, WN, NPL, 2, 1, 3, R2, PW), HGC_VP(KS, A, B, WM, WN, NPL, 1, 1, 3, R1, PW)
 // aligned-channel forms of one tile shape for input loads of 4, 2 and 1 pixels
 #define HGC_VX(KS, A, B, WM, WN, NPL, NST, R8, R4, R2, R1)                                      \
     HGC_V1(KS, A, B, WM, WN, NPL, 4, 1, NST, R4),                                               \
@@ -694,6 +896,17 @@ static const IgemmVariant g_variants[] = {
     HGC_VX(5, 2, 2, 1, 4, 2, 1, 1, 2, 3, 4),    // 5x5  64 ch x 256 px
     HGC_VR(5, 2, 2, 1, 4, 2, 1, 3, 4),
     HGC_VR(7, 1, 2, 1, 4, 2, 1, 3, 6),          // stem-like 7x7: 32 ch x 256 px
+    // small tiles with the loads two steps ahead (three weight buffers): few, latency-bound workgroups
+    HGC_VX(3, 1, 1, 1, 4, 4, 3, 1, 1, 2, 2),    //  32 ch x 128 px, 32 channels per step
+    HGC_VX(3, 1, 1, 1, 4, 2, 3, 1, 1, 1, 2),    //  32 ch x 128 px, 16 channels per step
+    HGC_VX(3, 2, 1, 1, 4, 4, 3, 1, 1, 2, 2),    //  64 ch x 128 px, 32 channels per step
+    HGC_VX(3, 1, 2, 1, 4, 2, 3, 1, 1, 2, 4),    //  32 ch x 256 px, 16 channels per step
+    // the same with four producer waves beside the four MFMA waves
+    HGC_VS(3, 1, 1, 1, 4, 4, 4, 1, 2, 2),       //  32 ch x 128 px, 32 channels per step
+    HGC_VS(3, 1, 1, 1, 4, 2, 4, 1, 1, 2),       //  32 ch x 128 px, 16 channels per step
+    HGC_VS(3, 2, 1, 1, 4, 4, 4, 1, 2, 2),       //  64 ch x 128 px, 32 channels per step
+    HGC_VS(3, 1, 2, 1, 4, 2, 4, 1, 2, 4),       //  32 ch x 256 px, 16 channels per step
+    HGC_VS(3, 1, 2, 1, 4, 4, 4, 2, 4, 4),       //  32 ch x 256 px, 32 channels per step
 };
 
 const IgemmVariant *HGC_IGEMM_ACCESSOR(int *count)

@@ -121,6 +121,39 @@ def test_every_tile_variant_agrees_with_the_oracle(oracle):
     assert seen >= 60
 
 
+def test_two_steps_ahead_pipeline_at_every_step_count(oracle):
+    """Instantiations that keep the loads two steps ahead: 1..6 channel blocks (odd and even
+    counts, the one- and two-step prologues and tails), whole and split reductions."""
+    ran = 0
+    try:
+        for packed in (False, True):
+            for v in range(128):
+                name = hgc.igemm_variant_name(v, packed)
+                if not name:
+                    break
+                targs = name[name.index("<") + 1:].replace(" ", "").split(",")
+                if targs[0] != "3" or targs[9] != "3":      # kernel extent 3, NSTAGE 3
+                    continue
+                cb = 8 * int(targs[5])
+                for nblocks in (1, 2, 3, 4, 5, 6):
+                    L = _layer((2, cb * nblocks - 8, 14, 24, 40, 3, 1, 1, 1))
+                    for ws in (False, True):
+                        if packed and not ws:
+                            continue
+                        hgc.set_forced_path(hgc.PATH_IGEMM_SPLITK if (ws and nblocks == 6) else hgc.PATH_IGEMM, v)
+                        p = hgc.conv2d_plan(L, ws, packed)
+                        if p.variant != v or p.path not in (hgc.PATH_IGEMM, hgc.PATH_IGEMM_SPLITK):
+                            continue
+                        say(f"[ahead2 variant {v} packed={packed}] {L} ws={ws} plan={p.as_dict()}")
+                        x, w, b = make_tensors(L, seed=100 + v + nblocks)
+                        y = run_layer(L, x, w, b, use_ws=ws, packed=packed)
+                        assert_full(oracle, L, x, w, b, y, tag=f"ahead2 variant {v} packed={packed} blocks={nblocks}")
+                        ran += 1
+    finally:
+        hgc.set_forced_path(hgc.PATH_AUTO)
+    assert ran >= 40
+
+
 def test_direct_and_mfma_paths_agree(oracle):
     L = _layer((2, 32, 20, 22, 64, 3, 1, 1, 1))
     x, w, b = make_tensors(L, seed=1)
