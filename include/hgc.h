@@ -30,7 +30,7 @@
  *
  * Ownership: the caller owns every buffer.  The library never allocates, frees,
  * copies to the host or synchronises; each call only enqueues kernels on
- * `stream` and returns.  x, w, b are read-only; every element of y is written
+ * `stream` and returns (one documented exception: hgc_conv2d_tune).  x, w, b are read-only; every element of y is written
  * exactly once; y must not overlap x, w, b or the workspace.  The descriptor is
  * read during the call only.  Calls are thread-safe.
  */
@@ -117,7 +117,8 @@ hgc_status hgc_conv2d_forward_ws(const hgc_conv2d_desc *desc, const void *x, con
 hgc_status hgc_conv2d_workspace_size(const hgc_conv2d_desc *desc, size_t *bytes_out);
 
 /*
- * The algorithm and launch shape a call would use.  with_workspace = 0 describes
+ * The algorithm and launch shape a call would use (16-byte aligned tensors assumed; a
+ * shape remembered by hgc_conv2d_tune is reported).  with_workspace = 0 describes
  * hgc_conv2d_forward, 1 hgc_conv2d_forward_ws, 3 hgc_conv2d_forward_packed.  Host-only.
  */
 hgc_status hgc_conv2d_plan(const hgc_conv2d_desc *desc, int32_t with_workspace, hgc_plan *plan_out);
@@ -143,6 +144,26 @@ hgc_status hgc_conv2d_pack_weights(const hgc_conv2d_desc *desc, const void *w, v
 hgc_status hgc_conv2d_forward_packed(const hgc_conv2d_desc *desc, const void *x, const void *w_packed,
                                      const void *b, void *y, void *workspace, size_t workspace_bytes,
                                      void *stream);
+
+/*
+ * Set-up-time measurement of the launch shape, the counterpart of packing the weights
+ * once: work done before inference so that none of it is left on the path (Section 3.3).
+ * Runs the implicit-GEMM launch shapes that the cost model ranks near its own choice on
+ * the caller's buffers, a few launches each, and remembers the fastest for later calls of
+ * hgc_conv2d_forward_ws (packed = 0) or hgc_conv2d_forward_packed (packed = 1, w = the
+ * packed buffer) with the same descriptor and tensor alignment in this process; a later
+ * call that brings a smaller workspace than the remembered shape needs falls back to the
+ * model's choice.  Unlike every other call this one creates and destroys two events and
+ * WAITS for the stream.  y and the workspace are overwritten; on return y holds the
+ * layer's output.  chosen_out (may be NULL) receives the shape now in effect.  Same
+ * errors, in the same order, as the forward call it tunes.  Descriptors that do not take
+ * the implicit-GEMM path are left alone.  hgc_conv2d_tune_reset forgets every
+ * remembered shape.  Both are thread-safe.
+ */
+hgc_status hgc_conv2d_tune(const hgc_conv2d_desc *desc, const void *x, const void *w, const void *b, void *y,
+                           void *workspace, size_t workspace_bytes, int32_t packed, void *stream,
+                           hgc_plan *chosen_out);
+void hgc_conv2d_tune_reset(void);
 
 /*
  * Test/diagnostic control: force one algorithm (HGC_PATH_*) for every later call
@@ -173,7 +194,7 @@ const char *hgc_last_launch_error(void);
 /*
  * Diagnostic: writes the template-argument prefix of implicit-GEMM instantiation
  * `variant` (hgc_plan.variant; packed = 1 for hgc_conv2d_forward_packed's table) as a
- * profiler prints it, e.g. "igemm_kernel<3, 1, 1, 1, 4, 4, 4, true, true, 2, 1".
+ * profiler prints it, e.g. "igemm_kernel<3, 1, 1, 1, 4, 4, 4, true, true, 2, 1, 0".
  * Returns the length, or -1 for a bad index or buffer.
  */
 int32_t hgc_igemm_variant_name(int32_t packed, int32_t variant, char *buf, int32_t buf_len);

@@ -92,6 +92,10 @@ def load():
     lib.hgc_conv2d_pack_weights.restype = ctypes.c_int32
     lib.hgc_conv2d_forward_packed.argtypes = [dp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
     lib.hgc_conv2d_forward_packed.restype = ctypes.c_int32
+    lib.hgc_conv2d_tune.argtypes = [dp, vp, vp, vp, vp, vp, ctypes.c_size_t, ctypes.c_int32, vp, ctypes.POINTER(Plan)]
+    lib.hgc_conv2d_tune.restype = ctypes.c_int32
+    lib.hgc_conv2d_tune_reset.argtypes = []
+    lib.hgc_conv2d_tune_reset.restype = None
     lib.hgc_set_forced_tiling.argtypes = [ctypes.c_int32, ctypes.c_int32]
     lib.hgc_set_forced_tiling.restype = None
     lib.hgc_status_string.argtypes = [ctypes.c_int32]
@@ -262,3 +266,39 @@ def conv2d_forward_packed(desc, x, w_packed, b=None, y=None, workspace=None):
     if st != 0:
         raise HgcError(st, "hgc_conv2d_forward_packed")
     return y
+
+
+def tune_raw(desc: Optional[ConvDesc], x: int, w: int, b: int, y: int, ws: int, ws_bytes: int, packed: bool,
+             stream: int = 0, plan: Optional[Plan] = None) -> int:
+    dref = ctypes.byref(desc) if desc is not None else None
+    pref = ctypes.byref(plan) if plan is not None else None
+    return int(load().hgc_conv2d_tune(dref, x or None, w or None, b or None, y or None, ws or None,
+                                      int(ws_bytes), 1 if packed else 0, stream or None, pref))
+
+
+def conv2d_tune(desc, x, w, b=None, y=None, workspace=None, packed: bool = False) -> Plan:
+    """hgc_conv2d_tune; w is the packed buffer when packed.  Returns the shape now in effect."""
+    import torch
+    d = ConvDesc.make(desc)
+    _check_tensor(x, "x", (d.N, d.C, d.H, d.W))
+    if d.bias:
+        if b is None:
+            raise ValueError("bias=1 needs b")
+        _check_tensor(b, "b", (d.num_output,))
+    if y is None:
+        y = torch.empty(d.out_shape(), dtype=torch.float16, device=x.device)
+    else:
+        _check_tensor(y, "y", d.out_shape())
+    ws_ptr, ws_bytes = 0, 0
+    if workspace is not None:
+        ws_ptr, ws_bytes = workspace.data_ptr(), workspace.numel() * workspace.element_size()
+    plan = Plan()
+    st = tune_raw(d, x.data_ptr(), w.data_ptr(), b.data_ptr() if (d.bias and b is not None) else 0,
+                  y.data_ptr(), ws_ptr, ws_bytes, packed, torch.cuda.current_stream(x.device).cuda_stream, plan)
+    if st != 0:
+        raise HgcError(st, "hgc_conv2d_tune")
+    return plan
+
+
+def conv2d_tune_reset() -> None:
+    load().hgc_conv2d_tune_reset()

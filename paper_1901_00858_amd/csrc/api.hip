@@ -9,6 +9,9 @@
 #include <cmath>
 #include <cstdio>
 #include <cstring>
+#include <map>
+#include <mutex>
+#include <vector>
 
 #include "hgc_internal.h"
 
@@ -21,6 +24,43 @@ static std::atomic<int> g_forced_log2_tw{-1};
 static std::atomic<int> g_forced_split{-1};
 
 static constexpr long long kMaxLds = 160 * 1024;
+
+// A launch shape of the implicit-GEMM path fixed from outside the cost model: by the
+// test controls or by a measurement (hgc_conv2d_tune).  -1 = let the model choose.
+struct Forced {
+    int variant = -1, log2_tw = -1, split = -1;
+    bool any() const { return variant >= 0 || log2_tw >= 0 || split >= 0; }
+};
+
+// Shapes found by hgc_conv2d_tune, keyed by everything the choice depends on.
+struct TuneKey {
+    int d[11];
+    int packed, with_ws, x_align, w_al16;
+    bool operator<(const TuneKey &o) const { return std::memcmp(this, &o, sizeof(*this)) < 0; }
+};
+static std::mutex g_tune_mutex;
+static std::map<TuneKey, Forced> g_tuned;
+static std::atomic<int> g_tuned_count{0};
+
+static TuneKey tune_key(const hgc_conv2d_desc &d, bool packed, bool with_ws, int x_align, bool w_al16)
+{
+    TuneKey k;
+    std::memset(&k, 0, sizeof(k));
+    const int v[11] = {d.N, d.C, d.H, d.W, d.num_output, d.kernel, d.stride, d.pad, d.group, d.bias, d.relu};
+    std::memcpy(k.d, v, sizeof(v));
+    k.packed = packed; k.with_ws = with_ws; k.x_align = x_align; k.w_al16 = w_al16;
+    return k;
+}
+
+static bool tuned_lookup(const TuneKey &k, Forced *f)
+{
+    if (g_tuned_count.load(std::memory_order_acquire) == 0) return false;
+    std::lock_guard<std::mutex> lock(g_tune_mutex);
+    auto it = g_tuned.find(k);
+    if (it == g_tuned.end()) return false;
+    *f = it->second;
+    return true;
+}
 
 static hgc_status validate(const hgc_conv2d_desc *d, Geometry *g)
 {
@@ -69,6 +109,7 @@ struct Plan {
     hgc_plan pub;
     ConvArgs args;
     const IgemmVariant *variant;
+    double cycles;       // the cost model's estimate (implicit-GEMM paths)
 };
 
 static void base_args(const Geometry &g, ConvArgs *a)
@@ -137,8 +178,9 @@ static double estimate_cycles(const Geometry &g, const Candidate &c)
 }
 
 static bool plan_igemm(const Geometry &g, bool with_ws, int x_align, bool w_al16, bool packed,
-                       int forced_variant, bool force_split, Plan *pl)
+                       const Forced &forced, bool force_split, Plan *pl)
 {
+    const int forced_variant = forced.variant;
     int nv = 0;
     const IgemmVariant *vs = packed ? igemm_variants_packed(&nv) : igemm_variants_raw(&nv);
     // widest input load: W and x's byte alignment / 2 must be multiples of the pixel count
@@ -161,8 +203,8 @@ static bool plan_igemm(const Geometry &g, bool with_ws, int x_align, bool w_al16
             if (v.xvec != xv || v.calign != want_cal) continue;
         }
         const int BN = v.BN();
-        const int f_tw = g_forced_log2_tw.load(std::memory_order_relaxed);
-        const int f_sp = g_forced_split.load(std::memory_order_relaxed);
+        const int f_tw = forced.log2_tw;
+        const int f_sp = forced.split;
         for (int j = 2; (1 << j) <= BN && j <= 9; ++j) {
             if (f_tw >= 0 && j != f_tw) continue;
             Candidate c;
@@ -207,6 +249,7 @@ static bool plan_igemm(const Geometry &g, bool with_ws, int x_align, bool w_al16
     pl->pub.tile_h = best.v->BN() >> a->log2_tw;
     pl->pub.split_k = a->split_k;
     pl->pub.variant = (int)(best.v - vs);
+    pl->cycles = best.cycles;
     pl->pub.grid = a->grid_blocks;
     pl->pub.block = best.v->threads();
     pl->pub.lds_bytes = best.lds;
@@ -215,7 +258,8 @@ static bool plan_igemm(const Geometry &g, bool with_ws, int x_align, bool w_al16
     return true;
 }
 
-static void make_plan(const Geometry &g0, bool with_ws, int x_align, bool w_al16, bool packed, Plan *pl)
+static void make_plan(const Geometry &g0, bool with_ws, int x_align, bool w_al16, bool packed, Plan *pl,
+                      const Forced *tuned = nullptr)
 {
     const Geometry g = kernel_geometry(g0);
     std::memset(pl, 0, sizeof(*pl));
@@ -223,7 +267,13 @@ static void make_plan(const Geometry &g0, bool with_ws, int x_align, bool w_al16
     pl->pub.Ho = g0.Ho; pl->pub.Wo = g0.Wo;
     pl->pub.split_k = 1;
     const int forced = g_forced_path.load(std::memory_order_relaxed);
-    const int fvar = g_forced_variant.load(std::memory_order_relaxed);
+    Forced fc;
+    fc.variant = g_forced_variant.load(std::memory_order_relaxed);
+    fc.log2_tw = g_forced_log2_tw.load(std::memory_order_relaxed);
+    fc.split = g_forced_split.load(std::memory_order_relaxed);
+    // a measured shape applies only while no test control is active
+    const bool use_tuned = tuned && forced == HGC_PATH_AUTO && !fc.any();
+    if (use_tuned) fc = *tuned;
     const bool depthwise_ok = (g.G == g.C && g.M == g.C && (g.k == 3 || g.k == 5));
 
     int path = forced;
@@ -240,29 +290,45 @@ static void make_plan(const Geometry &g0, bool with_ws, int x_align, bool w_al16
     }
     if (path == HGC_PATH_IGEMM || path == HGC_PATH_IGEMM_SPLITK) {
         const bool ws = with_ws && (forced != HGC_PATH_IGEMM);
-        if (plan_igemm(g, ws, x_align, w_al16, packed, fvar, forced == HGC_PATH_IGEMM_SPLITK && with_ws, pl))
+        if (plan_igemm(g, ws, x_align, w_al16, packed, fc, forced == HGC_PATH_IGEMM_SPLITK && with_ws, pl))
             return;
         base_args(g, &pl->args);
+        if (use_tuned) {     // the remembered shape does not fit this call (smaller workspace): plan afresh
+            make_plan(g0, with_ws, x_align, w_al16, packed, pl, nullptr);
+            return;
+        }
     }
     pl->pub.path = HGC_PATH_DIRECT;
     pl->pub.block = 256;
     pl->pub.grid = (int)std::min<long long>(1048576, ((long long)g.N * g.M * g.Ho * g.Wo + 255) / 256);
 }
 
-static hgc_status run(const hgc_conv2d_desc *desc, const void *x, const void *w, const void *b,
-                      void *y, void *ws, size_t ws_bytes, bool with_ws, bool packed, void *stream)
+// Validation, plan and kernel arguments of one call (no GPU work).  `shape` overrides the
+// remembered / modelled launch shape (used while tuning).
+static hgc_status prepare(const hgc_conv2d_desc *desc, const void *x, const void *w, const void *b, void *y,
+                          void *ws, size_t ws_bytes, bool with_ws, bool packed, const Forced *shape, Plan *plp)
 {
     if (!desc || !x || !w || !y) return HGC_ERR_NULL;
     if (desc->bias == 1 && !b) return HGC_ERR_NULL;
     Geometry g;
     hgc_status st = validate(desc, &g);
     if (st != HGC_OK) return st;
-    Plan pl;
+    Plan &pl = *plp;
     int x_align = 16;                            // byte alignment of x, capped at 16
     while (x_align > 2 && ((uintptr_t)x % x_align)) x_align >>= 1;
     const bool w_al16 = ((uintptr_t)w & 15) == 0;
     if (packed && ((uintptr_t)w & 255)) return HGC_ERR_ALIGNMENT;
-    make_plan(g, with_ws, x_align, w_al16, packed, &pl);
+    Forced tuned;
+    if (shape) {
+        make_plan(g, with_ws, x_align, w_al16, packed, &pl, shape);
+    } else if (tuned_lookup(tune_key(*desc, packed, with_ws, x_align, w_al16), &tuned)) {
+        make_plan(g, with_ws, x_align, w_al16, packed, &pl, &tuned);
+        // remembered with a larger workspace than this call brings: plan afresh
+        if (pl.pub.workspace_bytes > 0 && (!ws || (long long)ws_bytes < pl.pub.workspace_bytes))
+            make_plan(g, with_ws, x_align, w_al16, packed, &pl);
+    } else {
+        make_plan(g, with_ws, x_align, w_al16, packed, &pl);
+    }
     if (pl.pub.workspace_bytes > 0) {
         // the size reported to the caller assumed aligned tensors; an unaligned call
         // may need the same or less, never more (same tiles, same split rule)
@@ -290,7 +356,12 @@ static hgc_status run(const hgc_conv2d_desc *desc, const void *x, const void *w,
         while (ov > 1 && (wo % ov || (1 << a.log2_tw) % ov || ((uintptr_t)y % (2 * ov)))) ov >>= 1;
         a.out_vec = ov;
     }
-    hipStream_t s = static_cast<hipStream_t>(stream);
+    return HGC_OK;
+}
+
+static hipError_t enqueue(const Plan &pl, hipStream_t s)
+{
+    const ConvArgs &a = pl.args;
     hipError_t e;
     switch (pl.pub.path) {
     case HGC_PATH_DEPTHWISE:
@@ -305,8 +376,106 @@ static hgc_status run(const hgc_conv2d_desc *desc, const void *x, const void *w,
         e = launch_direct(a, s);
         break;
     }
+    return e;
+}
+
+static hgc_status run(const hgc_conv2d_desc *desc, const void *x, const void *w, const void *b,
+                      void *y, void *ws, size_t ws_bytes, bool with_ws, bool packed, void *stream)
+{
+    Plan pl;
+    const hgc_status st = prepare(desc, x, w, b, y, ws, ws_bytes, with_ws, packed, nullptr, &pl);
+    if (st != HGC_OK) return st;
+    const hipError_t e = enqueue(pl, static_cast<hipStream_t>(stream));
     g_last_hip_error = (int)e;
     return e == hipSuccess ? HGC_OK : HGC_ERR_LAUNCH;
+}
+
+// Measure the launch shapes the cost model ranks within a factor of the best and remember the
+// fastest.  Synchronises the stream; meant for set-up time, like the weight packing.
+static hgc_status tune(const hgc_conv2d_desc *desc, const void *x, const void *w, const void *b, void *y,
+                       void *ws, size_t ws_bytes, bool packed, hipStream_t s, hgc_plan *chosen)
+{
+    Plan base;
+    hgc_status st = prepare(desc, x, w, b, y, ws, ws_bytes, true, packed, nullptr, &base);
+    if (st != HGC_OK) return st;
+    if (chosen) *chosen = base.pub;
+    if (base.pub.path != HGC_PATH_IGEMM && base.pub.path != HGC_PATH_IGEMM_SPLITK) return HGC_OK;
+    if (g_forced_path.load(std::memory_order_relaxed) != HGC_PATH_AUTO) return HGC_OK;
+    int x_align = 16;
+    while (x_align > 2 && ((uintptr_t)x % x_align)) x_align >>= 1;
+    const bool w_al16 = ((uintptr_t)w & 15) == 0;
+    const TuneKey key = tune_key(*desc, packed, true, x_align, w_al16);
+    {   // start from the model's choice, not from an earlier measurement
+        std::lock_guard<std::mutex> lock(g_tune_mutex);
+        if (g_tuned.erase(key)) g_tuned_count.fetch_sub(1, std::memory_order_release);
+    }
+    st = prepare(desc, x, w, b, y, ws, ws_bytes, true, packed, nullptr, &base);
+    if (st != HGC_OK) return st;
+
+    struct Cand { Forced f; Plan pl; float us; };
+    std::vector<Cand> cands;
+    int nv = 0;
+    (void)(packed ? igemm_variants_packed(&nv) : igemm_variants_raw(&nv));
+    static const int splits[] = {1, 2, 3, 4, 6, 8, 12, 16, 32};
+    for (int v = 0; v < nv; ++v)
+        for (int j = 2; j <= 9; ++j)
+            for (int sp : splits) {
+                Cand c;
+                c.f.variant = v; c.f.log2_tw = j; c.f.split = sp;
+                if (prepare(desc, x, w, b, y, ws, ws_bytes, true, packed, &c.f, &c.pl) != HGC_OK) continue;
+                const hgc_plan &pp = c.pl.pub;
+                if (pp.path != HGC_PATH_IGEMM && pp.path != HGC_PATH_IGEMM_SPLITK) continue;
+                if (pp.variant != v || pp.tile_w != (1 << j) || pp.split_k != sp) continue;   // not this shape
+                if (c.pl.cycles > 2.5 * base.cycles) continue;
+                c.us = 0.0f;
+                cands.push_back(c);
+            }
+    if (cands.empty()) return HGC_OK;
+    hipEvent_t e0, e1;
+    if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess) return HGC_ERR_LAUNCH;
+    hipError_t err = hipSuccess;
+    auto measure = [&](Cand &c, int reps) {
+        for (int i = 0; i < 2 && err == hipSuccess; ++i) err = enqueue(c.pl, s);
+        if (err == hipSuccess) err = hipEventRecord(e0, s);
+        for (int i = 0; i < reps && err == hipSuccess; ++i) err = enqueue(c.pl, s);
+        if (err == hipSuccess) err = hipEventRecord(e1, s);
+        if (err == hipSuccess) err = hipEventSynchronize(e1);
+        float ms = 0.0f;
+        if (err == hipSuccess) err = hipEventElapsedTime(&ms, e0, e1);
+        c.us = ms * 1000.0f / reps;
+    };
+    for (Cand &c : cands) {
+        measure(c, 5);
+        if (err != hipSuccess) break;
+    }
+    if (err == hipSuccess) {
+        std::sort(cands.begin(), cands.end(), [](const Cand &a, const Cand &b) { return a.us < b.us; });
+        const size_t top = std::min<size_t>(cands.size(), 6);
+        for (size_t i = 0; i < top && err == hipSuccess; ++i) measure(cands[i], 25);
+        if (err == hipSuccess) {
+            Cand ref;                                // the model's own choice under the same clock
+            ref.pl = base;
+            measure(ref, 25);
+            size_t best = 0;
+            for (size_t i = 1; i < top; ++i)
+                if (cands[i].us < cands[best].us) best = i;
+            if (err == hipSuccess && cands[best].us < 0.97f * ref.us) {
+                std::lock_guard<std::mutex> lock(g_tune_mutex);
+                g_tuned[key] = cands[best].f;
+                g_tuned_count.store((int)g_tuned.size(), std::memory_order_release);
+                if (chosen) *chosen = cands[best].pl.pub;
+            }
+        }
+    }
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    // leave y holding the result of a complete, valid call
+    if (err == hipSuccess) {
+        Plan fin;
+        if (prepare(desc, x, w, b, y, ws, ws_bytes, true, packed, nullptr, &fin) == HGC_OK) err = enqueue(fin, s);
+    }
+    g_last_hip_error = (int)err;
+    return err == hipSuccess ? HGC_OK : HGC_ERR_LAUNCH;
 }
 
 }  // namespace hgc
@@ -357,7 +526,10 @@ hgc_status hgc_conv2d_plan(const hgc_conv2d_desc *desc, int32_t with_workspace, 
     hgc_status st = validate(desc, &g);
     if (st != HGC_OK) return st;
     Plan pl;
-    make_plan(g, (with_workspace & 1) != 0, 16, true, (with_workspace & 2) != 0, &pl);
+    const bool ws = (with_workspace & 1) != 0, packed = (with_workspace & 2) != 0;
+    Forced tuned;
+    if (tuned_lookup(tune_key(*desc, packed, ws, 16, true), &tuned)) make_plan(g, ws, 16, true, packed, &pl, &tuned);
+    else make_plan(g, ws, 16, true, packed, &pl);
     *plan_out = pl.pub;
     return HGC_OK;
 }
@@ -405,6 +577,21 @@ hgc_status hgc_conv2d_forward_packed(const hgc_conv2d_desc *desc, const void *x,
         if (validate(desc, &g) == HGC_OK && packed_layout(g).total > 0xFFFFFFF0LL) return HGC_ERR_TOO_LARGE;
     }
     return run(desc, x, w_packed, b, y, workspace, workspace_bytes, true, true, stream);
+}
+
+hgc_status hgc_conv2d_tune(const hgc_conv2d_desc *desc, const void *x, const void *w, const void *b, void *y,
+                           void *workspace, size_t workspace_bytes, int32_t packed, void *stream,
+                           hgc_plan *chosen_out)
+{
+    return tune(desc, x, w, b, y, workspace, workspace_bytes, packed != 0, static_cast<hipStream_t>(stream),
+                chosen_out);
+}
+
+void hgc_conv2d_tune_reset(void)
+{
+    std::lock_guard<std::mutex> lock(g_tune_mutex);
+    g_tuned.clear();
+    g_tuned_count.store(0, std::memory_order_release);
 }
 
 void hgc_set_forced_tiling(int32_t log2_tile_w, int32_t split_k)

@@ -115,6 +115,17 @@ def test_packed_entry_points_validate_on_the_host(lib):
     assert p.path in hgc.PATH_NAMES
 
 
+def test_tuning_call_validates_on_the_host(lib):
+    """hgc_conv2d_tune: same error order as the forward call, all before any GPU work."""
+    d = _d()
+    assert hgc.tune_raw(None, FAKE, FAKE, FAKE, FAKE, FAKE, 1 << 20, False) == -1
+    assert hgc.tune_raw(d, 0, FAKE, FAKE, FAKE, FAKE, 1 << 20, False) == -1
+    assert hgc.tune_raw(d, FAKE, FAKE, 0, FAKE, FAKE, 1 << 20, True) == -1       # bias=1 needs b
+    assert hgc.tune_raw(_d(stride=0), FAKE, FAKE, FAKE, FAKE, FAKE, 1 << 20, False) == -2
+    assert hgc.tune_raw(d, FAKE, FAKE + 16, FAKE, FAKE, FAKE, 1 << 20, True) == -6   # packed buffer alignment
+    hgc.conv2d_tune_reset()                                                       # harmless when empty
+
+
 def test_status_strings(lib):
     seen = {hgc.status_string(s) for s in (0, -1, -2, -3, -4, -5, -6)}
     assert len(seen) == 7 and hgc.status_string(0) == "ok"

@@ -154,6 +154,46 @@ def test_two_steps_ahead_pipeline_at_every_step_count(oracle):
     assert ran >= 40
 
 
+def test_tuned_launch_shapes_keep_parity(oracle):
+    """hgc_conv2d_tune remembers a measured shape: results stay within tolerance with it, the plan
+    query reports it, a call with a smaller workspace falls back, and reset restores the model's plan."""
+    import torch
+    cases = [(1, 64, 28, 28, 96, 3, 1, 1, 1), (1, 256, 14, 14, 256, 3, 1, 1, 1), (2, 96, 14, 14, 160, 1, 1, 0, 1)]
+    try:
+        for t in cases:
+            L = _layer(t)
+            x, w, b = make_tensors(L, seed=7)
+            xd, wd, bd = (torch.from_numpy(a).cuda() for a in (x, w, b))
+            for packed in (False, True):
+                hgc.conv2d_tune_reset()
+                before = hgc.conv2d_plan(L, True, packed).as_dict()
+                wbuf = hgc.conv2d_pack_weights(L, wd) if packed else wd
+                need = hgc.conv2d_workspace_size(L)
+                big = torch.empty(max(need, 16 << 20), dtype=torch.uint8, device="cuda")
+                y = torch.empty(L.y_shape, dtype=torch.float16, device="cuda")
+                say(f"[tune] {L} packed={packed} model plan {before}")
+                chosen = hgc.conv2d_tune(L, xd, wbuf, bd, y, big, packed=packed).as_dict()
+                torch.cuda.synchronize()
+                assert_full(oracle, L, x, w, b, y.cpu().numpy(), tag=f"tune output packed={packed}")
+                assert hgc.conv2d_plan(L, True, packed).as_dict() == chosen
+                fwd = hgc.conv2d_forward_packed if packed else hgc.conv2d_forward_ws
+                # the remembered shape, with the workspace it was measured with
+                y.view(torch.int16).fill_(0x7E00)
+                fwd(L, xd, wbuf, bd, y, big)
+                torch.cuda.synchronize()
+                assert_full(oracle, L, x, w, b, y.cpu().numpy(), tag=f"tuned {chosen} packed={packed}")
+                # a workspace of only the advertised size: falls back where the shape needs more
+                small = torch.empty(max(need, 1), dtype=torch.uint8, device="cuda")
+                y.view(torch.int16).fill_(0x7E00)
+                fwd(L, xd, wbuf, bd, y, small)
+                torch.cuda.synchronize()
+                assert_full(oracle, L, x, w, b, y.cpu().numpy(), tag=f"tuned, small workspace packed={packed}")
+                hgc.conv2d_tune_reset()
+                assert hgc.conv2d_plan(L, True, packed).as_dict() == before
+    finally:
+        hgc.conv2d_tune_reset()
+
+
 def test_direct_and_mfma_paths_agree(oracle):
     L = _layer((2, 32, 20, 22, 64, 3, 1, 1, 1))
     x, w, b = make_tensors(L, seed=1)
