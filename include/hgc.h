@@ -166,6 +166,16 @@ hgc_status hgc_conv2d_tune(const hgc_conv2d_desc *desc, const void *x, const voi
 void hgc_conv2d_tune_reset(void);
 
 /*
+ * Restores a launch shape found earlier (hgc_plan.variant, log2 of hgc_plan.tile_w,
+ * hgc_plan.split_k as reported by hgc_conv2d_tune), so that a process need not measure
+ * again: remembered for calls with 16-byte aligned tensors like a shape that
+ * hgc_conv2d_tune found.  Host-only.  HGC_ERR_BAD_DESC if the descriptor is invalid or the
+ * shape is not one of its implicit-GEMM launch shapes.
+ */
+hgc_status hgc_conv2d_set_launch_shape(const hgc_conv2d_desc *desc, int32_t packed, int32_t variant,
+                                       int32_t log2_tile_w, int32_t split_k);
+
+/*
  * Test/diagnostic control: force one algorithm (HGC_PATH_*) for every later call
  * in this process where it applies, or HGC_PATH_AUTO to restore the heuristic.
  * A forced path that cannot run a descriptor falls back to HGC_PATH_DIRECT.

@@ -94,6 +94,8 @@ def load():
     lib.hgc_conv2d_forward_packed.restype = ctypes.c_int32
     lib.hgc_conv2d_tune.argtypes = [dp, vp, vp, vp, vp, vp, ctypes.c_size_t, ctypes.c_int32, vp, ctypes.POINTER(Plan)]
     lib.hgc_conv2d_tune.restype = ctypes.c_int32
+    lib.hgc_conv2d_set_launch_shape.argtypes = [dp, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32]
+    lib.hgc_conv2d_set_launch_shape.restype = ctypes.c_int32
     lib.hgc_conv2d_tune_reset.argtypes = []
     lib.hgc_conv2d_tune_reset.restype = None
     lib.hgc_set_forced_tiling.argtypes = [ctypes.c_int32, ctypes.c_int32]
@@ -302,3 +304,11 @@ def conv2d_tune(desc, x, w, b=None, y=None, workspace=None, packed: bool = False
 
 def conv2d_tune_reset() -> None:
     load().hgc_conv2d_tune_reset()
+
+
+def conv2d_set_launch_shape(desc, packed: bool, variant: int, log2_tile_w: int, split_k: int) -> None:
+    d = ConvDesc.make(desc)
+    st = load().hgc_conv2d_set_launch_shape(ctypes.byref(d), 1 if packed else 0, int(variant), int(log2_tile_w),
+                                            int(split_k))
+    if st != 0:
+        raise HgcError(st, "hgc_conv2d_set_launch_shape")

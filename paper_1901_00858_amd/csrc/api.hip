@@ -41,6 +41,8 @@ struct TuneKey {
 static std::mutex g_tune_mutex;
 static std::map<TuneKey, Forced> g_tuned;
 static std::atomic<int> g_tuned_count{0};
+// bumped whenever a remembered shape or a test control changes: plans cached before are stale
+static std::atomic<unsigned> g_plan_epoch{1};
 
 static TuneKey tune_key(const hgc_conv2d_desc &d, bool packed, bool with_ws, int x_align, bool w_al16)
 {
@@ -124,11 +126,23 @@ static void base_args(const Geometry &g, ConvArgs *a)
 static int ceil_div(long long a, long long b) { return (int)((a + b - 1) / b); }
 
 // ---- choice of tile shape, output window and reduction split -----------------
-// A candidate is (kernel instantiation, window tile_h x tile_w, split).  Its cost
-// is a coarse cycle estimate: workgroups run in rounds over the 256 CUs; one
-// workgroup costs a fixed ramp plus, per channel block, the larger of its MFMA
-// time and its staging time, plus the epilogue.  The constants were fitted to
-// rocprofv3 kernel durations on MI355X; only the ranking matters.
+// A candidate is (kernel instantiation, window tile_h x tile_w, split).  Its cost is
+// an estimate of the launch's duration built from what bounds one channel block of one
+// workgroup on a CU:
+//   MF  MFMA issue: 32 cycles per 32x32x16 MFMA, waves of a SIMD one after the other;
+//   TA  the vector-memory path: bytes of patch rows (whole cache lines) and weights at
+//       64 B/cycle, or 16 cycles per wave-wide instruction, whichever is larger;
+//   LR  fragment reads from LDS, 1 KiB per ds_read_b128 at 256 B/cycle, more for
+//       windows narrower than 32 columns (a 32-lane read then spans several patch rows);
+//   X   transposes and LDS stores of the staged patch.
+// A lone workgroup executes these one after the other (waves that both stage and
+// compute) or side by side (producer and consumer waves); k co-resident workgroups
+// share the CU's units.  Around the K loop there is a fixed ramp and the epilogue; a
+// split reduction adds the partial-sum traffic and a second launch; nothing runs
+// faster than its HBM traffic.  The coefficients, and one correction factor per tile
+// family, were fitted to measured durations of every launch shape of the AlexNet,
+// VGG-16, ResNet-50 and MobileNet-v1 layer shapes at batch 1 and at batch 16/32/64 on
+// MI355X; only the ranking matters.
 struct Candidate {
     const IgemmVariant *v;
     int log2_tw, tiles_w, tiles_h, tiles_m, PH, PWU, nsteps, split, steps_per_split;
@@ -136,45 +150,75 @@ struct Candidate {
     double cycles;
 };
 
+struct FamilyBias { int ks, a, b, wm, wn, npl, nstage, pw; double log_factor; };
+static const FamilyBias kFamilyBias[] = {
+    {1, 2, 1, 1, 4, 8, 1, 0, 0.003},  {1, 2, 1, 1, 4, 8, 2, 0, -0.078}, {1, 2, 2, 1, 4, 4, 1, 0, 0.064},
+    {1, 2, 2, 1, 4, 8, 1, 0, 0.018},  {1, 2, 2, 1, 4, 8, 2, 0, -0.030}, {1, 2, 4, 1, 4, 4, 1, 0, 0.400},
+    {1, 2, 4, 1, 4, 8, 1, 0, 0.188},  {1, 2, 4, 2, 2, 8, 2, 0, 0.052},  {1, 4, 1, 1, 4, 8, 1, 0, 0.052},
+    {1, 4, 4, 1, 4, 4, 1, 0, 0.259},  {3, 1, 1, 1, 4, 2, 3, 0, -0.036}, {3, 1, 1, 1, 4, 2, 3, 4, -0.021},
+    {3, 1, 1, 1, 4, 4, 2, 0, -0.096}, {3, 1, 1, 1, 4, 4, 3, 0, -0.038}, {3, 1, 1, 1, 4, 4, 3, 4, -0.028},
+    {3, 1, 2, 1, 4, 2, 2, 0, -0.054}, {3, 1, 2, 1, 4, 2, 3, 0, -0.007}, {3, 1, 2, 1, 4, 2, 3, 4, 0.014},
+    {3, 1, 2, 1, 4, 4, 3, 4, 0.036},  {3, 1, 2, 2, 2, 4, 2, 0, -0.090}, {3, 2, 1, 1, 4, 4, 2, 0, -0.105},
+    {3, 2, 1, 1, 4, 4, 3, 4, -0.083}, {3, 2, 2, 1, 4, 2, 2, 0, 0.070},  {3, 2, 2, 2, 2, 2, 2, 0, 0.072},
+    {3, 2, 4, 2, 2, 2, 2, 0, 0.152},  {3, 2, 4, 2, 4, 2, 2, 0, -0.035}, {5, 2, 2, 1, 4, 2, 1, 0, -0.114},
+    {7, 1, 2, 1, 4, 2, 1, 0, -0.140},
+};
+
 static double estimate_cycles(const Geometry &g, const Candidate &c)
 {
     const IgemmVariant &v = *c.v;
-    const int T = v.ks * v.ks;
-    const int NW = v.waves_m * v.waves_n, NT = 64 * v.stage_waves();
-    const int RPW = v.BM() / NW;
-    const int WLR = (RPW * v.npl * T + 63) / 64, WIR = (RPW * v.npl + 63) / 64;
+    // fitted coefficients (see above)
+    const double c_mf = 0.9237, c_ta = 0.6632, c_lr = 3.1395, c_x = 2.6165, c_sync = 191.74, c_fix = 1758.4,
+                 c_epi = 4.4905, c_lat = -179.41, c_split = 5466.6, c_splitb = 1.3992, c_narrow = 0.1912,
+                 t_launch = 2.5414, c_ser_ta = 0.6344, c_chain = -0.0395, c_spec = 317.28, c_hbm = 4.3629;
+    const int T = v.ks * v.ks, A = v.wm_blocks, B = v.wn_blocks;
+    const int NW = v.waves_m * v.waves_n, NWS = v.stage_waves(), NT = 64 * NWS;
+    const int RPW = v.BM() / NWS, CB = 8 * v.npl;
+    const bool wdma = v.packed || v.calign;
+    const int WLR = wdma ? (RPW * v.npl * T + 63) / 64 : 0, WIR = (RPW * v.npl + 63) / 64;
     const int items = v.npl * c.PH * (c.PWU / v.xvec);
     const int Rx = (items + NT - 1) / NT;
-    // phases of one K step of one wave, in core cycles (fitted to in-kernel timestamps)
-    static const double xcost[9] = {0, 45, 70, 0, 160, 0, 0, 0, 600};   // transpose + LDS stores per item
-    double L = 25.0 * (8 * Rx + (v.packed || v.calign ? WLR : 0));     // issue of the vector-memory loads
-    double X = Rx * xcost[v.xvec];
+    const double mf_wave = 32.0 * A * B * T * v.npl / 2;
+    const double wsimd_c = std::max(1.0, NW / 4.0);                     // MFMA waves per SIMD
+    const double mf_simd = mf_wave * wsimd_c;
+    const double bytes_x = (double)CB * c.PH * (2.0 * c.PWU + 64.0);
+    const double bytes_w = (double)v.BM() * CB * T * 2.0;
+    const double TA = std::max((bytes_x + bytes_w) / 64.0, 16.0 * NWS * (8.0 * Rx + WLR));
+    const double narrow = 1.0 + c_narrow * std::max(0, 5 - c.log2_tw);
+    const double LR = NW * (A + B) * (double)T * v.npl / 2 * 4.0 * narrow;
+    double X = Rx * (v.xvec == 4 ? 160.0 : v.xvec == 2 ? 70.0 : 45.0);
     if (!v.packed) X += v.calign ? 1400.0 * WIR : 250.0 * T * WIR;      // regroup / scalar fetch of weights
-    // windows narrower than 32 columns split a 32-lane operand read over several patch rows
-    // (LDS bank conflicts, shorter global segments)
-    static const double narrow[10] = {2.0, 2.0, 1.5, 1.3, 1.12, 1.0, 1.0, 1.0, 1.0, 1.0};
-    const double C = 32.0 * v.wm_blocks * v.wn_blocks * T * (v.npl / 2) / 0.75 * narrow[c.log2_tw];
-    L *= narrow[c.log2_tw];
-    const double w = NW / 4.0;                                          // waves per SIMD of one workgroup
-    const double mfma_simd = C * std::max(1.0, w);
-    const double serial = L + C + X + (v.nstage == 1 ? 2500.0 : 300.0); // one buffer: the load latency is exposed
+    const double chain = c_chain * (A * B == 1 ? mf_wave : 0.0);
+    double serial;
+    if (v.prod_waves == 0)
+        serial = c_ser_ta * TA + c_mf * mf_simd + chain + c_x * X + c_sync + (v.nstage == 1 ? c_lat : 0.0);
+    else
+        serial = std::max(c_mf * mf_wave + chain + c_spec, c_ser_ta * TA + c_x * X) + c_sync;
     // co-residency: registers, LDS, threads
-    const int regs = 16 * v.wm_blocks * v.wn_blocks + 90;
+    const int regs = 16 * A * B + 90;
     const int waves_simd = std::max(1, std::min(8, 512 / regs));
-    int k = (int)std::min<double>(waves_simd / std::max(1.0, w), (double)(kMaxLds / std::max<long long>(c.lds, 1)));
-    k = std::max(1, std::min(k, 2048 / v.threads()));
+    const double wsimd = std::max(1.0, (NW + v.prod_waves) / 4.0);
+    long long k = std::min<long long>((long long)(waves_simd / wsimd), kMaxLds / std::max<long long>(c.lds, 1));
+    k = std::max<long long>(1, std::min<long long>(k, 2048 / v.threads()));
     const long long wgs = c.grid * c.split;
     const long long on_cu = (wgs + 255) / 256;                          // workgroups the busiest CU gets
-    k = (int)std::min<long long>(k, on_cu);
-    const double step_time = std::max(k * mfma_simd, serial);
-    const double fixed = 6000.0 + 60.0 * v.wm_blocks * v.wn_blocks + 400.0 + serial;   // ramp, first stage, epilogue
-    const double rounds = std::ceil((double)on_cu / k);
-    double total = rounds * (fixed + c.steps_per_split * step_time);
-    if (c.split > 1) {
-        const double ws_bytes = 4.0 * c.split * g.N * (double)g.M * g.Ho * g.Wo;
-        total += 8000.0 + 2.0 * ws_bytes / 2000.0;      // write + read of the partial sums, second launch
-    }
-    return total;
+    k = std::min(k, on_cu);
+    const double step = std::max(std::max(k * c_mf * mf_simd, k * c_ta * TA), std::max(k * c_lr * LR, serial));
+    const double fixed = c_fix + c_epi * A * B * 64.0 + serial + c_lat;
+    const double rounds = std::ceil((double)on_cu / (double)k);
+    double total = rounds * (fixed + c.steps_per_split * step);
+    const double outs = (double)g.N * g.M * g.Ho * g.Wo;
+    if (c.split > 1) total += c_split + c_splitb * (4.0 * c.split * outs) / 2000.0;
+    const double x_bytes = 2.0 * g.N * g.C * g.H * g.W, w_bytes = 2.0 * g.M * (double)g.Kg;
+    const double hbm_us = (x_bytes * std::min(c.tiles_m, 2) + 2.0 * outs + 8.0 * w_bytes) / (c_hbm * 1e6);
+    double us = std::max(total / 1700.0, hbm_us) + t_launch;
+    for (const FamilyBias &f : kFamilyBias)
+        if (f.ks == v.ks && f.a == A && f.b == B && f.wm == v.waves_m && f.wn == v.waves_n && f.npl == v.npl &&
+            f.nstage == v.nstage && f.pw == v.prod_waves) {
+            us *= std::exp(f.log_factor);
+            break;
+        }
+    return us;
 }
 
 static bool plan_igemm(const Geometry &g, bool with_ws, int x_align, bool w_al16, bool packed,
@@ -321,13 +365,42 @@ static hgc_status prepare(const hgc_conv2d_desc *desc, const void *x, const void
     Forced tuned;
     if (shape) {
         make_plan(g, with_ws, x_align, w_al16, packed, &pl, shape);
-    } else if (tuned_lookup(tune_key(*desc, packed, with_ws, x_align, w_al16), &tuned)) {
-        make_plan(g, with_ws, x_align, w_al16, packed, &pl, &tuned);
-        // remembered with a larger workspace than this call brings: plan afresh
-        if (pl.pub.workspace_bytes > 0 && (!ws || (long long)ws_bytes < pl.pub.workspace_bytes))
-            make_plan(g, with_ws, x_align, w_al16, packed, &pl);
     } else {
-        make_plan(g, with_ws, x_align, w_al16, packed, &pl);
+        // Ranking the launch shapes costs tens of microseconds, more than a small layer's
+        // kernel: each thread keeps the plans of the descriptors it has seen.
+        struct Slot { TuneKey key; unsigned epoch; Plan plan; };
+        constexpr unsigned kSlots = 256, kWays = 8;       // open addressing, kWays probes
+        static thread_local Slot slots[kSlots];
+        static thread_local unsigned victim = 0;
+        const TuneKey key = tune_key(*desc, packed, with_ws, x_align, w_al16);
+        unsigned h = 2166136261u;
+        for (size_t i = 0; i < sizeof(key) / sizeof(int); ++i)
+            h = (h ^ (unsigned)reinterpret_cast<const int *>(&key)[i]) * 16777619u;
+        h ^= h >> 15;
+        const unsigned epoch = g_plan_epoch.load(std::memory_order_acquire);
+        Slot *hit = nullptr, *free_slot = nullptr;
+        for (unsigned w = 0; w < kWays; ++w) {
+            Slot &c = slots[(h + w) & (kSlots - 1)];
+            if (c.epoch != epoch) {
+                if (!free_slot) free_slot = &c;
+            } else if (std::memcmp(&c.key, &key, sizeof(key)) == 0) {
+                hit = &c;
+                break;
+            }
+        }
+        if (!hit) {
+            hit = free_slot ? free_slot : &slots[(h + (victim++ % kWays)) & (kSlots - 1)];
+            if (tuned_lookup(key, &tuned)) make_plan(g, with_ws, x_align, w_al16, packed, &hit->plan, &tuned);
+            else make_plan(g, with_ws, x_align, w_al16, packed, &hit->plan);
+            hit->key = key;
+            hit->epoch = epoch;
+        }
+        Slot &slot = *hit;
+        pl = slot.plan;
+        // remembered with a larger workspace than this call brings: plan afresh
+        if (pl.pub.workspace_bytes > 0 && (!ws || (long long)ws_bytes < pl.pub.workspace_bytes) &&
+            tuned_lookup(key, &tuned))
+            make_plan(g, with_ws, x_align, w_al16, packed, &pl);
     }
     if (pl.pub.workspace_bytes > 0) {
         // the size reported to the caller assumed aligned tensors; an unaligned call
@@ -408,6 +481,7 @@ static hgc_status tune(const hgc_conv2d_desc *desc, const void *x, const void *w
     {   // start from the model's choice, not from an earlier measurement
         std::lock_guard<std::mutex> lock(g_tune_mutex);
         if (g_tuned.erase(key)) g_tuned_count.fetch_sub(1, std::memory_order_release);
+        g_plan_epoch.fetch_add(1, std::memory_order_release);
     }
     st = prepare(desc, x, w, b, y, ws, ws_bytes, true, packed, nullptr, &base);
     if (st != HGC_OK) return st;
@@ -463,6 +537,7 @@ static hgc_status tune(const hgc_conv2d_desc *desc, const void *x, const void *w
                 std::lock_guard<std::mutex> lock(g_tune_mutex);
                 g_tuned[key] = cands[best].f;
                 g_tuned_count.store((int)g_tuned.size(), std::memory_order_release);
+                g_plan_epoch.fetch_add(1, std::memory_order_release);
                 if (chosen) *chosen = cands[best].pl.pub;
             }
         }
@@ -538,7 +613,9 @@ int32_t hgc_set_forced_path(int32_t path, int32_t tile_variant)
 {
     if (path < HGC_PATH_AUTO || path > HGC_PATH_DEPTHWISE) path = HGC_PATH_AUTO;
     g_forced_variant.store(tile_variant, std::memory_order_relaxed);
-    return g_forced_path.exchange(path, std::memory_order_relaxed);
+    const int32_t before = g_forced_path.exchange(path, std::memory_order_relaxed);
+    g_plan_epoch.fetch_add(1, std::memory_order_release);
+    return before;
 }
 
 hgc_status hgc_conv2d_packed_weights_size(const hgc_conv2d_desc *desc, size_t *bytes_out)
@@ -587,17 +664,41 @@ hgc_status hgc_conv2d_tune(const hgc_conv2d_desc *desc, const void *x, const voi
                 chosen_out);
 }
 
+hgc_status hgc_conv2d_set_launch_shape(const hgc_conv2d_desc *desc, int32_t packed, int32_t variant,
+                                       int32_t log2_tile_w, int32_t split_k)
+{
+    if (!desc) return HGC_ERR_NULL;
+    Geometry g;
+    hgc_status st = validate(desc, &g);
+    if (st != HGC_OK) return st;
+    Forced f;
+    f.variant = variant; f.log2_tw = log2_tile_w; f.split = split_k;
+    Plan pl;
+    make_plan(g, true, 16, true, packed != 0, &pl, &f);
+    const hgc_plan &pp = pl.pub;
+    if ((pp.path != HGC_PATH_IGEMM && pp.path != HGC_PATH_IGEMM_SPLITK) || pp.variant != variant ||
+        pp.tile_w != (1 << log2_tile_w) || pp.split_k != split_k)
+        return HGC_ERR_BAD_DESC;                 // not a launch shape of this descriptor
+    std::lock_guard<std::mutex> lock(g_tune_mutex);
+    g_tuned[tune_key(*desc, packed != 0, true, 16, true)] = f;
+    g_tuned_count.store((int)g_tuned.size(), std::memory_order_release);
+    g_plan_epoch.fetch_add(1, std::memory_order_release);
+    return HGC_OK;
+}
+
 void hgc_conv2d_tune_reset(void)
 {
     std::lock_guard<std::mutex> lock(g_tune_mutex);
     g_tuned.clear();
     g_tuned_count.store(0, std::memory_order_release);
+    g_plan_epoch.fetch_add(1, std::memory_order_release);
 }
 
 void hgc_set_forced_tiling(int32_t log2_tile_w, int32_t split_k)
 {
     g_forced_log2_tw.store(log2_tile_w, std::memory_order_relaxed);
     g_forced_split.store(split_k, std::memory_order_relaxed);
+    g_plan_epoch.fetch_add(1, std::memory_order_release);
 }
 
 const char *hgc_status_string(hgc_status status)

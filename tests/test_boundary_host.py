@@ -126,6 +126,30 @@ def test_tuning_call_validates_on_the_host(lib):
     hgc.conv2d_tune_reset()                                                       # harmless when empty
 
 
+def test_launch_shapes_can_be_restored_on_the_host(lib):
+    """hgc_conv2d_set_launch_shape: accepts exactly the shapes the planner can produce."""
+    import math
+    L = (1, 64, 28, 28, 96, 3, 1, 1, 1, 1, 1)
+    try:
+        hgc.conv2d_tune_reset()
+        model = hgc.conv2d_plan(L, True, True).as_dict()
+        assert model["path"] in (hgc.PATH_IGEMM, hgc.PATH_IGEMM_SPLITK)
+        d = hgc.ConvDesc.make(L)
+        assert lib.hgc_conv2d_set_launch_shape(None, 1, 0, 5, 1) == -1
+        assert lib.hgc_conv2d_set_launch_shape(ctypes.byref(d), 1, 9999, 5, 1) == -2
+        assert lib.hgc_conv2d_set_launch_shape(ctypes.byref(d), 1, model["variant"], 30, 1) == -2
+        # another window of the same instantiation
+        other = 4 if model["tile_w"] != 16 else 3
+        hgc.conv2d_set_launch_shape(L, True, model["variant"], other, 1)
+        now = hgc.conv2d_plan(L, True, True).as_dict()
+        assert (now["variant"], now["tile_w"], now["split_k"]) == (model["variant"], 1 << other, 1)
+        assert hgc.conv2d_plan(L, True, False).as_dict() == hgc.conv2d_plan(L, True, False).as_dict()
+        hgc.conv2d_tune_reset()
+        assert hgc.conv2d_plan(L, True, True).as_dict() == model
+    finally:
+        hgc.conv2d_tune_reset()
+
+
 def test_status_strings(lib):
     seen = {hgc.status_string(s) for s in (0, -1, -2, -3, -4, -5, -6)}
     assert len(seen) == 7 and hgc.status_string(0) == "ok"
