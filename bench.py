@@ -22,7 +22,7 @@ PEAK_MFMA_F16 = 2516.6e12     # MI355X dense FP16 MFMA FLOP/s
 PEAK_HBM = 8.0e12             # MI355X HBM3E B/s
 
 # (config, batch, entry, path, variant) -> HBM bytes per launch of the dominant kernel, from
-# the rocprofv3 --pmc summaries under profiles/ (see the design doc for the scaling)
+# the rocprofv3 --pmc summaries under profiles/ (each states its calibration copy and commands)
 TRAFFIC_BYTES_PER_LAUNCH = {
     # mean over the kernel's launches of a step: FETCH_SIZE KiB x 2.0 (copy calibration) + WRITE_SIZE KiB x 1.0
     # N=1: conv5..conv8 (three launches of grid 224, one of grid 112)

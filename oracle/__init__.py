@@ -22,6 +22,7 @@ import numpy as np
 
 _DIR = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_DIR, "conv2d_oracle.c")
+_SRC_IP = os.path.join(_DIR, "inner_product_oracle.c")
 _LIB = os.path.join(_DIR, "libhgo.so")
 _lib = None
 
@@ -31,8 +32,9 @@ ABS_TOL = 1e-3
 
 def build(force: bool = False) -> str:
     """Compile the oracle with gcc (-O2 -fopenmp).  Returns the library path."""
-    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
-        cmd = ["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-std=c11", "-o", _LIB, _SRC, "-lm"]
+    newest = max(os.path.getmtime(_SRC), os.path.getmtime(_SRC_IP))
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < newest:
+        cmd = ["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-std=c11", "-o", _LIB, _SRC, _SRC_IP, "-lm"]
         subprocess.run(cmd, check=True)
     return _LIB
 
@@ -51,6 +53,8 @@ def _load():
         lib.hgo_conv2d_forward.restype = ctypes.c_int
         lib.hgo_conv2d_points.argtypes = [i32p, u16p, u16p, u16p, ctypes.c_longlong, i32p, f64p, f64p]
         lib.hgo_conv2d_points.restype = ctypes.c_int
+        lib.hgo_inner_product_forward.argtypes = [i32p, u16p, u16p, u16p, f64p, f64p]
+        lib.hgo_inner_product_forward.restype = ctypes.c_int
         lib.hgo_num_threads.restype = ctypes.c_int
         lib.hgo_set_num_threads.argtypes = [ctypes.c_int]
         _lib = lib
@@ -127,6 +131,36 @@ def conv2d_points(desc, x, w, b, idx):
                                pre.ctypes.data_as(f64p), mag.ctypes.data_as(f64p))
     if rc:
         raise ValueError(f"oracle rejected the request (rc={rc})")
+    return pre, mag
+
+
+def inner_product_forward(desc, x, w, b=None):
+    """Inner-product layer (inner_product_oracle.c): desc = (N, K, M, bias, relu), x [N][K], w [M][K], b [M].
+
+    Returns (pre, mag), FP64 arrays of shape [N][M]: bias + sum of products, and sum of |products|.
+    """
+    lib = _load()
+    d = [int(v) for v in desc]
+    if len(d) != 5:
+        raise ValueError("desc = (N, K, M, bias, relu)")
+    if d[0] < 1 or d[1] < 1 or d[2] < 1 or d[3] not in (0, 1) or d[4] not in (0, 1):
+        raise ValueError("bad inner-product descriptor")
+    if d[3] and b is None:
+        raise ValueError("bias=1 needs b")
+    x = np.asarray(x)
+    w = np.asarray(w)
+    if x.size != d[0] * d[1] or w.size != d[2] * d[1] or (d[3] and np.asarray(b).size != d[2]):
+        raise ValueError("tensor sizes do not match the descriptor")
+    dk = (ctypes.c_int32 * 5)(*d)
+    xk, xp = _u16(x)
+    wk, wp = _u16(w)
+    bk, bp = _u16(b if d[3] else None)
+    pre = np.empty((d[0], d[2]), dtype=np.float64)
+    mag = np.empty((d[0], d[2]), dtype=np.float64)
+    f64p = ctypes.POINTER(ctypes.c_double)
+    rc = lib.hgo_inner_product_forward(dk, xp, wp, bp, pre.ctypes.data_as(f64p), mag.ctypes.data_as(f64p))
+    if rc:
+        raise ValueError(f"oracle rejected the descriptor (rc={rc})")
     return pre, mag
 
 

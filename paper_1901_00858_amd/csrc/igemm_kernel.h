@@ -29,13 +29,15 @@
 //   Input: each item is XVEC pixels x 8 channels; eight loads (one per channel
 // plane of NCHW, coalesced along W) are transposed in registers with v_perm_b32
 // into XVEC units.  Items past the end of the patch write a dump unit.
-//   Weights: each wave owns BM/NW rows; it fetches their contiguous CB*k*k-half
+//   Weights: each staging wave owns a share of the BM rows; it fetches their contiguous CB*k*k-half
 // runs with 16-byte LDS-direct loads (buffer_load_dwordx4 ... lds) into its own
 // slice of the LDS weight buffer, reads them back one (row, plane) per lane and
 // writes the regrouped units over the same slice.  LDS operations of one wave
 // execute in order, so no barrier is needed inside the wave.
-// With NSTAGE = 2 the LDS buffers are double: the loads of step s+1 are issued
-// before the MFMAs of step s and are stored to the other buffer after them.
+// Pipelines over the K steps (NSTAGE, PW): 1 = one LDS buffer; 2 = double-buffered LDS,
+// the loads of step s+1 are issued among the MFMAs of step s and stored to the other
+// buffer; 3 = three weight and two patch buffers with the loads two steps ahead; PW > 0
+// adds PW producer waves that only stage while the other waves only run MFMAs.
 #pragma once
 #include <atomic>
 #include <type_traits>
