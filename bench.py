@@ -197,6 +197,37 @@ def main() -> int:
         torch.cuda.synchronize()
         ms_tuned = timed(args.entry, args.steps, args.warmup)
 
+    # ---- the classifier's inner-product layers (the next row after the convolution stack): HBM-bound,
+    # reported beside the headline, never part of `value` ----
+    fc_report = None
+    fc_shapes = {"vgg16": [("fc6", 25088, 4096), ("fc7", 4096, 4096), ("fc8", 4096, 1000)],
+                 "alexnet": [("fc6", 9216, 4096), ("fc7", 4096, 4096), ("fc8", 4096, 1000)]}.get(args.config)
+    if fc_shapes:
+        from workloads import uniform01, normal01
+        fc_report = []
+        for name, K, M in fc_shapes:
+            Nb = args.batch
+            xh = (2.0 * uniform01(7, 0, Nb * K) - 1.0).astype(np.float16).reshape(Nb, K)
+            wh = (normal01(7, 1, M * K) * np.sqrt(2.0 / K)).astype(np.float16).reshape(M, K)
+            bh = (0.2 * uniform01(7, 2, M) - 0.1).astype(np.float16)
+            xd, wd, bd = (torch.from_numpy(a).to(dev) for a in (xh, wh, bh))
+            yd = torch.empty((Nb, M), dtype=torch.float16, device=dev)
+            d = hgc.InnerProductDesc(Nb, K, M, 1, 1)
+            call = lambda: hgc.inner_product_forward_raw(d, xd.data_ptr(), wd.data_ptr(), bd.data_ptr(), yd.data_ptr(), sh)
+            for _ in range(5):
+                assert call() == 0
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            for _ in range(20):
+                call()
+            e1.record(stream)
+            e1.synchronize()
+            us = e0.elapsed_time(e1) * 1e3 / 20
+            nbytes = 2 * (M * K + Nb * K + M + Nb * M)
+            fc_report.append({"layer": name, "N": Nb, "K": K, "M": M, "us": us, "GB/s": nbytes / us / 1e3,
+                              "frac_of_hbm_peak": nbytes / us / 1e3 / (PEAK_HBM / 1e9),
+                              "algorithmic_bytes": nbytes})
+
     # ---- the oracle, as it stands, timed on the host cores (a reported baseline) ----
     cpu = None
     if not args.no_cpu:
@@ -232,6 +263,7 @@ def main() -> int:
         "caller_layout_weights": None if ms_other is None else {
             "entry": "hgc_conv2d_forward_ws", "ms_per_step": ms_other,
             "value": flops_step / (ms_other * 1e-3) / 1e12, "unit": "TFLOP/s"},
+        "inner_product_layers": fc_report,
         "roofline": roof,
         "cpu_baseline": cpu,
     }

@@ -192,6 +192,34 @@ int32_t hgc_set_forced_path(int32_t path, int32_t tile_variant);
  */
 void hgc_set_forced_tiling(int32_t log2_tile_w, int32_t split_k);
 
+/*
+ * Inner-product (fully connected) layer forward, the other layer the paper names as
+ * accumulating many values (Section 3.1), with the same rules as the convolution: FP16
+ * tensors used as they are, FP32 accumulation, one rounding to FP16 at the store,
+ * optional fused bias and ReLU:
+ *
+ *   y[n][m] = act( b[m] + sum_{k<K} w[m][k] * x[n][k] )
+ *
+ * x[N][K] (an image's values in memory order: a [N][C][H][W] tensor with K = C*H*W can be
+ * passed as it is), w[num_output][K] (Caffe's layout), b[num_output], y[N][num_output]:
+ * dense row-major FP16 in device memory, caller-owned; y must not overlap the inputs.
+ * desc: host.  Enqueues on `stream` and returns; no workspace.  Errors, in this order and
+ * before any GPU work: HGC_ERR_NULL (desc, x, w or y NULL; b NULL with bias = 1),
+ * HGC_ERR_BAD_DESC (N, K or num_output < 1; bias or relu not 0/1), HGC_ERR_TOO_LARGE (a
+ * tensor with more than 2^31 - 1 elements); then HGC_ERR_LAUNCH.  Results are
+ * deterministic.  Bases need 2-byte alignment; 16-byte aligned bases with K % 8 == 0
+ * take the fast path.
+ */
+typedef struct hgc_inner_product_desc {
+    int32_t N;              /* images                                                   */
+    int32_t K;              /* inputs per image                                         */
+    int32_t num_output;     /* M                                                        */
+    int32_t bias;           /* 0 or 1; b may be NULL iff 0                              */
+    int32_t relu;           /* 0 or 1                                                   */
+} hgc_inner_product_desc;
+hgc_status hgc_inner_product_forward(const hgc_inner_product_desc *desc, const void *x, const void *w,
+                                     const void *b, void *y, void *stream);
+
 /* Static, NUL-terminated description of a status code. */
 const char *hgc_status_string(hgc_status status);
 

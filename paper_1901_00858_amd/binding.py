@@ -49,6 +49,20 @@ class ConvDesc(ctypes.Structure):
         return (self.N, self.num_output, ho, wo)
 
 
+class InnerProductDesc(ctypes.Structure):
+    """hgc_inner_product_desc: five int32 fields in host memory."""
+    _fields_ = [(n, ctypes.c_int32) for n in ("N", "K", "num_output", "bias", "relu")]
+
+    @classmethod
+    def make(cls, desc) -> "InnerProductDesc":
+        if isinstance(desc, cls):
+            return desc
+        vals = [int(v) for v in desc]
+        if len(vals) != 5:
+            raise ValueError("desc = (N, K, num_output, bias, relu)")
+        return cls(*vals)
+
+
 class Plan(ctypes.Structure):
     """hgc_plan."""
     _fields_ = [(n, ctypes.c_int32) for n in
@@ -100,6 +114,8 @@ def load():
     lib.hgc_conv2d_tune_reset.restype = None
     lib.hgc_set_forced_tiling.argtypes = [ctypes.c_int32, ctypes.c_int32]
     lib.hgc_set_forced_tiling.restype = None
+    lib.hgc_inner_product_forward.argtypes = [ctypes.POINTER(InnerProductDesc), vp, vp, vp, vp, vp]
+    lib.hgc_inner_product_forward.restype = ctypes.c_int32
     lib.hgc_status_string.argtypes = [ctypes.c_int32]
     lib.hgc_status_string.restype = ctypes.c_char_p
     lib.hgc_version.restype = ctypes.c_int32
@@ -312,3 +328,31 @@ def conv2d_set_launch_shape(desc, packed: bool, variant: int, log2_tile_w: int, 
                                             int(split_k))
     if st != 0:
         raise HgcError(st, "hgc_conv2d_set_launch_shape")
+
+
+def inner_product_forward_raw(desc: Optional[InnerProductDesc], x: int, w: int, b: int, y: int, stream: int = 0) -> int:
+    dref = ctypes.byref(desc) if desc is not None else None
+    return int(load().hgc_inner_product_forward(dref, x or None, w or None, b or None, y or None, stream or None))
+
+
+def inner_product_forward(desc, x, w, b=None, y=None):
+    """hgc_inner_product_forward: x [N][K] (or any shape with N*K elements), w [M][K], b [M] -> y [N][M]."""
+    import torch
+    d = InnerProductDesc.make(desc)
+    for t, name, count in ((x, "x", d.N * d.K), (w, "w", d.num_output * d.K)):
+        _check_tensor(t, name)
+        if t.numel() != count:
+            raise ValueError(f"{name} has {t.numel()} elements, the descriptor needs {count}")
+    if d.bias:
+        if b is None:
+            raise ValueError("bias=1 needs b")
+        _check_tensor(b, "b", (d.num_output,))
+    if y is None:
+        y = torch.empty((d.N, d.num_output), dtype=torch.float16, device=x.device)
+    else:
+        _check_tensor(y, "y", (d.N, d.num_output))
+    st = inner_product_forward_raw(d, x.data_ptr(), w.data_ptr(), b.data_ptr() if (d.bias and b is not None) else 0,
+                                   y.data_ptr(), torch.cuda.current_stream(x.device).cuda_stream)
+    if st != 0:
+        raise HgcError(st, "hgc_inner_product_forward")
+    return y

@@ -25,6 +25,8 @@ static std::atomic<int> g_forced_split{-1};
 
 static constexpr long long kMaxLds = 160 * 1024;
 
+void set_last_hip_error(hipError_t e) { g_last_hip_error = (int)e; }
+
 // A launch shape of the implicit-GEMM path fixed from outside the cost model: by the
 // test controls or by a measurement (hgc_conv2d_tune).  -1 = let the model choose.
 struct Forced {

@@ -101,6 +101,9 @@ PackedLayout packed_layout(const Geometry &g);
 hipError_t launch_pack_weights(const Geometry &g, const PackedLayout &pl, const uint16_t *w, uint8_t *packed,
                                hipStream_t stream);
 
+// records the runtime error behind the calling thread's latest HGC_ERR_LAUNCH (hgc_last_launch_error)
+void set_last_hip_error(hipError_t e);
+
 hipError_t launch_direct(const ConvArgs &a, hipStream_t stream);
 hipError_t launch_depthwise(const ConvArgs &a, hipStream_t stream);
 hipError_t launch_splitk_reduce(const ConvArgs &a, hipStream_t stream);

@@ -1,0 +1,178 @@
+// Inner-product (fully connected) layer forward in FP16 for gfx950:
+//   y[n][m] = act( b[m] + sum_{k<K} w[m][k] * x[n][k] ),  x [N][K], w [M][K], y [N][M].
+// The paper names this layer as one where FP16 accumulation overflows (Section 3.1), so
+// products are accumulated in FP32 and the result is rounded to FP16 once, at the store;
+// weights are used as they arrive, no conversion pass (Section 3.3).
+//
+// At the batch sizes of inference the layer is bound by reading w once from HBM (2*M*K
+// bytes against 2*N*M*K FLOP), so this is a streaming kernel, not a GEMM: a wave owns R
+// rows of w and NB images; its 64 lanes walk K in 16-byte steps (one fully coalesced 1 KiB
+// segment of a row per instruction), multiply with v_dot2_f32_f16 (FP32 accumulate) and
+// reduce across the lanes at the end.  Rows of x are re-read by every wave; they stay
+// in L2.  More than 8 images are processed in passes of 8 (w is then read once per pass).
+#include "hgc_internal.h"
+
+namespace hgc {
+
+typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+struct IpArgs {
+    const uint16_t *x, *w, *b;
+    uint16_t *y;
+    int N, K, M, n0, bias, relu;
+    uint32_t x_bytes, w_bytes;
+};
+
+__device__ __forceinline__ float dot2(uint32_t a, uint32_t c, float acc)
+{
+    return __builtin_amdgcn_fdot2(__builtin_bit_cast(half2_t, a), __builtin_bit_cast(half2_t, c), acc, false);
+}
+
+__device__ __forceinline__ float dot8(const u32x4 a, const u32x4 c, float acc)
+{
+    acc = dot2(a.x, c.x, acc);
+    acc = dot2(a.y, c.y, acc);
+    acc = dot2(a.z, c.z, acc);
+    return dot2(a.w, c.w, acc);
+}
+
+// NB images per pass, R rows per wave.  VEC: K % 8 == 0 and 16-byte aligned bases (16-byte
+// loads), else element loads.
+template <int NB, int R, bool VEC>
+__global__ __launch_bounds__(256) void inner_product_kernel(const IpArgs p)
+{
+    const int lane = threadIdx.x & 63;
+    const int wave = blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int m0 = wave * R;
+    if (m0 >= p.M) return;
+    const int K = p.K;
+    float acc[R][NB];
+#pragma unroll
+    for (int r = 0; r < R; ++r)
+#pragma unroll
+        for (int i = 0; i < NB; ++i) acc[r][i] = 0.0f;
+
+    if (VEC) {
+        // buffer loads: rows past M and images past N use an out-of-range offset and read zero
+        const __amdgpu_buffer_rsrc_t rx = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t *>(p.x), 0, p.x_bytes, 0x00020000);
+        const __amdgpu_buffer_rsrc_t rw = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t *>(p.w), 0, p.w_bytes, 0x00020000);
+        uint32_t wo[R], xo[NB];
+#pragma unroll
+        for (int r = 0; r < R; ++r) wo[r] = (m0 + r < p.M) ? 2u * (uint32_t)((m0 + r) * K) : 0xFFFFFFFFu;
+#pragma unroll
+        for (int i = 0; i < NB; ++i) xo[i] = (p.n0 + i < p.N) ? 2u * (uint32_t)((p.n0 + i) * K) : 0xFFFFFFFFu;
+        // the same number of iterations for every lane; a lane past the end of the row reads zeros
+        const int iters = (K + 511) / 512;
+#pragma unroll 2
+        for (int it = 0; it < iters; ++it) {
+            const int k = it * 512 + lane * 8;
+            const bool in_row = k < K;
+            const uint32_t ko = 2u * (uint32_t)k;
+            u32x4 wv[R], xv[NB];
+#pragma unroll
+            for (int r = 0; r < R; ++r)
+                wv[r] = __builtin_amdgcn_raw_buffer_load_b128(rw, (in_row && wo[r] != 0xFFFFFFFFu) ? wo[r] + ko : 0xFFFFFFFFu, 0, 0);
+#pragma unroll
+            for (int i = 0; i < NB; ++i)
+                xv[i] = __builtin_amdgcn_raw_buffer_load_b128(rx, (in_row && xo[i] != 0xFFFFFFFFu) ? xo[i] + ko : 0xFFFFFFFFu, 0, 0);
+#pragma unroll
+            for (int r = 0; r < R; ++r)
+#pragma unroll
+                for (int i = 0; i < NB; ++i) acc[r][i] = dot8(wv[r], xv[i], acc[r][i]);
+        }
+    } else {
+        for (int k = lane; k < K; k += 64) {
+            float wv[R], xv[NB];
+#pragma unroll
+            for (int r = 0; r < R; ++r)
+                wv[r] = (m0 + r < p.M) ? (float)__builtin_bit_cast(_Float16, p.w[(size_t)(m0 + r) * K + k]) : 0.0f;
+#pragma unroll
+            for (int i = 0; i < NB; ++i)
+                xv[i] = (p.n0 + i < p.N) ? (float)__builtin_bit_cast(_Float16, p.x[(size_t)(p.n0 + i) * K + k]) : 0.0f;
+#pragma unroll
+            for (int r = 0; r < R; ++r)
+#pragma unroll
+                for (int i = 0; i < NB; ++i) acc[r][i] = fmaf(wv[r], xv[i], acc[r][i]);
+        }
+    }
+    // sum over the 64 lanes (fixed butterfly order: results are deterministic)
+#pragma unroll
+    for (int r = 0; r < R; ++r)
+#pragma unroll
+        for (int i = 0; i < NB; ++i) {
+            float v = acc[r][i];
+#pragma unroll
+            for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off, 64);
+            acc[r][i] = v;
+        }
+    if (lane == 0) {
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            const int m = m0 + r;
+            if (m >= p.M) continue;
+            const float bv = p.bias ? (float)__builtin_bit_cast(_Float16, p.b[m]) : 0.0f;
+#pragma unroll
+            for (int i = 0; i < NB; ++i) {
+                const int n = p.n0 + i;
+                if (n >= p.N) continue;
+                float v = acc[r][i] + bv;
+                if (p.relu) v = fmaxf(v, 0.0f);
+                p.y[(size_t)n * p.M + m] = __builtin_bit_cast(uint16_t, (_Float16)v);
+            }
+        }
+    }
+}
+
+template <int NB, int R, bool VEC>
+static hipError_t launch_ip(const IpArgs &a, hipStream_t s)
+{
+    const int waves = (a.M + R - 1) / R;
+    hipLaunchKernelGGL((inner_product_kernel<NB, R, VEC>), dim3((unsigned)((waves + 3) / 4)), dim3(256), 0, s, a);
+    return hipGetLastError();
+}
+
+template <int NB>
+static hipError_t launch_ip_nb(const IpArgs &a, bool vec, int rows, hipStream_t s)
+{
+    if (vec) return rows == 2 ? launch_ip<NB, 2, true>(a, s) : launch_ip<NB, 1, true>(a, s);
+    return launch_ip<NB, 1, false>(a, s);
+}
+
+}  // namespace hgc
+
+using namespace hgc;
+
+extern "C" hgc_status hgc_inner_product_forward(const hgc_inner_product_desc *desc, const void *x, const void *w,
+                                                const void *b, void *y, void *stream)
+{
+    if (!desc || !x || !w || !y) return HGC_ERR_NULL;
+    if (desc->bias == 1 && !b) return HGC_ERR_NULL;
+    if (desc->N < 1 || desc->K < 1 || desc->num_output < 1) return HGC_ERR_BAD_DESC;
+    if ((desc->bias != 0 && desc->bias != 1) || (desc->relu != 0 && desc->relu != 1)) return HGC_ERR_BAD_DESC;
+    const long long lim = 0x7FFFFFFFLL;
+    const long long N = desc->N, K = desc->K, M = desc->num_output;
+    if (N * K > lim || M * K > lim || N * M > lim) return HGC_ERR_TOO_LARGE;
+    IpArgs a;
+    a.x = static_cast<const uint16_t *>(x);
+    a.w = static_cast<const uint16_t *>(w);
+    a.b = static_cast<const uint16_t *>(b);
+    a.y = static_cast<uint16_t *>(y);
+    a.N = desc->N; a.K = desc->K; a.M = desc->num_output; a.n0 = 0; a.bias = desc->bias; a.relu = desc->relu;
+    a.x_bytes = (uint32_t)(2 * N * K);
+    a.w_bytes = (uint32_t)(2 * M * K);
+    const bool vec = (K % 8 == 0) && (((uintptr_t)x | (uintptr_t)w) & 15) == 0;
+    // two rows per wave once there are enough rows to fill the chip with one-row waves twice over
+    const int rows = M >= 2048 ? 2 : 1;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    hipError_t e = hipSuccess;
+    for (int n0 = 0; n0 < desc->N && e == hipSuccess; n0 += 8) {
+        a.n0 = n0;
+        const int nb = desc->N - n0;
+        if (nb >= 8) e = launch_ip_nb<8>(a, vec, rows, s);
+        else if (nb > 2) e = nb > 4 ? launch_ip_nb<8>(a, vec, rows, s) : launch_ip_nb<4>(a, vec, rows, s);
+        else e = nb == 2 ? launch_ip_nb<2>(a, vec, rows, s) : launch_ip_nb<1>(a, vec, rows, s);
+    }
+    set_last_hip_error(e);
+    return e == hipSuccess ? HGC_OK : HGC_ERR_LAUNCH;
+}

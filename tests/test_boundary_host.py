@@ -38,6 +38,7 @@ def test_every_declared_symbol_is_exported(lib):
 def test_struct_layouts_match_header(lib):
     assert ctypes.sizeof(ConvDesc) == 44
     assert ctypes.sizeof(hgc.Plan) == 56
+    assert ctypes.sizeof(hgc.InnerProductDesc) == 20
 
 
 GOOD = (1, 4, 8, 8, 4, 3, 1, 1, 1, 1, 1)
@@ -148,6 +149,23 @@ def test_launch_shapes_can_be_restored_on_the_host(lib):
         assert hgc.conv2d_plan(L, True, True).as_dict() == model
     finally:
         hgc.conv2d_tune_reset()
+
+
+def test_inner_product_validates_on_the_host(lib):
+    """hgc_inner_product_forward: NULL, then BAD_DESC, then TOO_LARGE, all before any GPU work."""
+    ip = hgc.InnerProductDesc
+    good = ip(2, 64, 10, 1, 0)
+    assert hgc.inner_product_forward_raw(None, FAKE, FAKE, FAKE, FAKE) == -1
+    assert hgc.inner_product_forward_raw(good, 0, FAKE, FAKE, FAKE) == -1
+    assert hgc.inner_product_forward_raw(good, FAKE, 0, FAKE, FAKE) == -1
+    assert hgc.inner_product_forward_raw(good, FAKE, FAKE, FAKE, 0) == -1
+    assert hgc.inner_product_forward_raw(good, FAKE, FAKE, 0, FAKE) == -1          # bias=1 needs b
+    assert hgc.inner_product_forward_raw(ip(0, 64, 10, 0, 0), 0, FAKE, FAKE, FAKE) == -1   # NULL wins
+    for bad in (ip(0, 64, 10, 0, 0), ip(2, 0, 10, 0, 0), ip(2, 64, 0, 0, 0), ip(2, 64, 10, 2, 0), ip(2, 64, 10, 0, -1)):
+        assert hgc.inner_product_forward_raw(bad, FAKE, FAKE, FAKE, FAKE) == -2
+    assert hgc.inner_product_forward_raw(ip(1, 1 << 16, 1 << 16, 0, 0), FAKE, FAKE, FAKE, FAKE) == -3
+    assert hgc.inner_product_forward_raw(ip(1 << 16, 1 << 16, 1, 0, 0), FAKE, FAKE, FAKE, FAKE) == -3
+    assert hgc.inner_product_forward_raw(ip(1 << 16, 1, 1 << 16, 0, 0), FAKE, FAKE, FAKE, FAKE) == -3
 
 
 def test_status_strings(lib):
