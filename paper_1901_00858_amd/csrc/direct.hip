@@ -227,28 +227,64 @@ hipError_t launch_depthwise(const ConvArgs &a, hipStream_t stream)
 }
 
 // Sum the FP32 slices of a split reduction in slice order (deterministic), then
-// bias, ReLU and the one rounding to FP16.
+// bias, ReLU and the one rounding to FP16.  The job is tiny and latency-bound: a thread
+// owns V consecutive outputs and has the loads of up to eight slices in flight at once
+// (the additions still happen in slice order).
+template <int V>
 __global__ __launch_bounds__(256) void splitk_reduce_kernel(const ConvArgs p)
 {
+    typedef float fvec __attribute__((ext_vector_type(V)));
     const long long total = (long long)p.N * p.M * p.Ho * p.Wo;
     const int HoWo = p.Ho * p.Wo;
-    for (long long o = (long long)blockIdx.x * 256 + threadIdx.x; o < total;
-         o += (long long)gridDim.x * 256) {
-        float acc = 0.0f;
-        for (int k = 0; k < p.split_k; ++k) acc += p.ws[(size_t)k * total + o];
-        const int m = (int)((o / HoWo) % p.M);
-        if (p.bias) acc += h2f(p.b[m]);
-        if (p.relu) acc = fmaxf(acc, 0.0f);
-        p.y[o] = f2h(acc);
+    const long long o = ((long long)blockIdx.x * 256 + threadIdx.x) * V;
+    if (o >= total) return;
+    const fvec *src = reinterpret_cast<const fvec *>(p.ws + o);
+    const size_t stride = (size_t)total / V;      // total % V == 0 (checked by the launcher)
+    float acc[V];
+#pragma unroll
+    for (int v = 0; v < V; ++v) acc[v] = 0.0f;
+    for (int k0 = 0; k0 < p.split_k; k0 += 8) {
+        fvec part[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k)
+            if (k0 + k < p.split_k) part[k] = src[(size_t)(k0 + k) * stride];
+#pragma unroll
+        for (int k = 0; k < 8; ++k)
+            if (k0 + k < p.split_k) {
+#pragma unroll
+                for (int v = 0; v < V; ++v) acc[v] += V == 1 ? ((const float *)&part[k])[0] : part[k][v];
+            }
+    }
+    // V consecutive outputs lie in one channel's plane when HoWo % V == 0 (checked by the launcher)
+    const int m = (int)((o / HoWo) % p.M);
+    const float bias = p.bias ? h2f(p.b[m]) : 0.0f;
+    uint16_t out[V];
+#pragma unroll
+    for (int v = 0; v < V; ++v) {
+        float r = acc[v] + bias;
+        if (p.relu) r = fmaxf(r, 0.0f);
+        out[v] = f2h(r);
+    }
+    if (V == 4) {
+        *reinterpret_cast<uint2 *>(p.y + o) = make_uint2(out[0] | ((uint32_t)out[1 % V] << 16),
+                                                         out[2 % V] | ((uint32_t)out[3 % V] << 16));
+    } else {
+#pragma unroll
+        for (int v = 0; v < V; ++v) p.y[o + v] = out[v];
     }
 }
 
 hipError_t launch_splitk_reduce(const ConvArgs &a, hipStream_t stream)
 {
     const long long total = (long long)a.N * a.M * a.Ho * a.Wo;
-    long long blocks = (total + 255) / 256;
-    if (blocks > 65536) blocks = 65536;
-    hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, a);
+    const bool vec = ((a.Ho * a.Wo) % 4 == 0) && (((uintptr_t)a.ws & 15) == 0) && (((uintptr_t)a.y & 7) == 0);
+    if (vec) {
+        const long long blocks = (total / 4 + 255) / 256;
+        hipLaunchKernelGGL(splitk_reduce_kernel<4>, dim3((unsigned)blocks), dim3(256), 0, stream, a);
+    } else {
+        const long long blocks = (total + 255) / 256;
+        hipLaunchKernelGGL(splitk_reduce_kernel<1>, dim3((unsigned)blocks), dim3(256), 0, stream, a);
+    }
     return hipGetLastError();
 }
 
