@@ -81,8 +81,9 @@ struct IgemmVariant {
         const long long wu = igemm_w_units(ks, wm_blocks, waves_m, stage_waves(), npl), xu = npl * PH * PWU + 8;
         // nstage 3: three weight buffers, two patch buffers (the patch waits in registers one step longer)
         const long long main = 16LL * (nstage == 3 ? 3 * wu + 2 * xu : nstage * (wu + xu));
-        const long long epi = 84LL * 32 * wm_blocks * waves_m * waves_n;   // transpose tile + bias per wave
-        return main > epi ? main : epi;
+        const long long epi = 80LL * 32 * wm_blocks * waves_m * waves_n;   // transpose tile per wave
+        const long long bias = 128LL * wm_blocks * waves_m * waves_n;      // FP32 bias of each wave's rows
+        return bias + (main > epi ? main : epi);
     }
 };
 

@@ -207,7 +207,11 @@ __global__ __launch_bounds__(64 * (WAVES_M * WAVES_N + PW)) void igemm_kernel(co
     static_assert(BM % NWS == 0 && (RPW & (RPW - 1)) == 0, "rows per wave must be a power of two");
     static_assert(W_UNITS == igemm_w_units(KS, A, WAVES_M, NWS, NPL), "host and kernel disagree on LDS");
 
-    extern __shared__ u32x4 lds[];
+    // LDS: [bias of every MFMA wave's rows, FP32][stage buffers ...]; the epilogue's transpose
+    // tiles reuse the stage buffers
+    constexpr int BIAS_UNITS = NW * 8 * A;       // 32*A floats per wave
+    extern __shared__ u32x4 lds_raw[];
+    u32x4 *const lds = lds_raw + BIAS_UNITS;
     const int X_UNITS = NPL * p.PH * p.PWU + 8;  // + dump units (one item's worth) for staging items past the end
     const int stage_units = W_UNITS + X_UNITS;   // [stage]{ W[wave]{[T][NPL][RPW]} , X[NPL][PH][PWU], dump }
     const int dump_unit = X_UNITS - 8;
@@ -429,13 +433,38 @@ __global__ __launch_bounds__(64 * (WAVES_M * WAVES_N + PW)) void igemm_kernel(co
     }
     const int plane_pair_stride = 2 * PH * PWU;
 
+    // The accumulators start from the bias (FP32), so the epilogue has no addition left.  A lane
+    // fetches the bias of one of its wave's rows early; init_acc(), called once the first stage's
+    // loads are under way, passes the values through the wave's private LDS words to the lanes
+    // that hold those rows (LDS operations of one wave execute in order: no barrier).  A split
+    // reduction adds the bias in its reduce kernel and starts from zero.
+    typedef float __attribute__((ext_vector_type(4), may_alias)) floatx4;
+    constexpr int BROWS = (32 * A + 63) / 64;
+    float bias_row[BROWS];
+#pragma unroll
+    for (int r = 0; r < BROWS; ++r) {
+        const int ml = m0 + wm * (32 * A) + lane + 64 * r;
+        bias_row[r] = (!SPLITK && p.bias && wave < NW && lane + 64 * r < 32 * A && ml < Mg)
+                          ? (float)__builtin_bit_cast(_Float16, p.b[g * Mg + ml]) : 0.0f;
+    }
     floatx16 acc[A][B];
+    auto init_acc = [&]() {
+        f32_alias *bw = reinterpret_cast<f32_alias *>(lds_raw) + (wave < NW ? wave : 0) * (32 * A);
 #pragma unroll
-    for (int i = 0; i < A; ++i)
+        for (int r = 0; r < BROWS; ++r)
+            if (lane + 64 * r < 32 * A) bw[lane + 64 * r] = bias_row[r];
+        asm volatile("" ::: "memory");
 #pragma unroll
-        for (int j = 0; j < B; ++j)
+        for (int i = 0; i < A; ++i) {
+            floatx4 bv[4];                       // rows 32i + 8q + 4lh + (0..3)
 #pragma unroll
-            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
+            for (int q = 0; q < 4; ++q) bv[q] = *reinterpret_cast<const floatx4 *>(bw + 32 * i + 8 * q + 4 * lh);
+#pragma unroll
+            for (int j = 0; j < B; ++j)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) acc[i][j][e] = bv[e >> 2][e & 3];
+        }
+    };
 
     // One K step: T taps x NPL/2 plane pairs, walked in two halves.  An iteration of a
     // large tile (A*B >= 4 MFMAs) hides the latency of the next iteration's ds_reads, so
@@ -582,6 +611,7 @@ __global__ __launch_bounds__(64 * (WAVES_M * WAVES_N + PW)) void igemm_kernel(co
             }
             return;                               // the epilogue belongs to the consumers
         }
+        init_acc();
         lds_barrier();                          // the first step is staged
         int wi = 0, par = 0;
         for (int st = st0; st < st1; ++st) {
@@ -627,6 +657,7 @@ __global__ __launch_bounds__(64 * (WAVES_M * WAVES_N + PW)) void igemm_kernel(co
         }
         store_x(st0, xbuf0, xreg[0]);
         store_w(st0, lds, xbuf0);
+        init_acc();
         lds_barrier();
         int wi = 0;
         for (int st = st0; st < st1; st += 2) {
@@ -643,6 +674,7 @@ __global__ __launch_bounds__(64 * (WAVES_M * WAVES_N + PW)) void igemm_kernel(co
         wait_vmem();
         store_x(st0, lds + W_UNITS, xreg[0]);
         store_w(st0, lds, lds + W_UNITS);
+        init_acc();
         lds_barrier();
         int cur = 0;
         for (int st = st0; st + 1 < st1; ++st, cur ^= 1) {
@@ -676,6 +708,7 @@ __global__ __launch_bounds__(64 * (WAVES_M * WAVES_N + PW)) void igemm_kernel(co
     } else {
         u32x4 *wl = lds, *xl = lds + W_UNITS;
         load_x(st0, xreg[0]);
+        init_acc();
         for (int st = st0; st < st1; ++st) {
             lds_barrier();                      // everyone is done reading the buffers
             load_w(st, wl);
@@ -698,9 +731,9 @@ __global__ __launch_bounds__(64 * (WAVES_M * WAVES_N + PW)) void igemm_kernel(co
     // channel row 8*(e/4) + 4*lh + e%4 and pixel column l32 of that block ----
     const int HoWo = p.Ho * p.Wo;
     // The last MFMAs may still be in flight.  The compiler pads MFMA -> accumulator-read
-    // hazards along the fall-through path only; a taken branch (for instance around the
-    // bias load) reached the first accumulator read too early and saw it without the last
-    // MFMA's contribution.  32 wait states cover the longest MFMA on any path.
+    // hazards along the fall-through path only; a taken branch just before the epilogue
+    // reached the first accumulator read too early and saw it without the last MFMA's
+    // contribution.  32 wait states cover the longest MFMA on any path.
     __builtin_amdgcn_sched_barrier(0);           // nothing, MFMAs included, moves across the padding
     asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
     __builtin_amdgcn_sched_barrier(0);
@@ -722,29 +755,17 @@ __global__ __launch_bounds__(64 * (WAVES_M * WAVES_N + PW)) void igemm_kernel(co
         }
         return;
     }
-    // Bias, ReLU, one rounding to FP16; then each wave transposes its tile through LDS
+    // The bias is already in the accumulators.  One rounding to FP16 (two rows per packed
+    // conversion), ReLU as a packed maximum; then each wave transposes its tile through LDS
     // (2-byte writes, 16-byte reads) so that a lane holds 8 consecutive pixels of one
     // output row and the global stores are 16, 8 or 4 bytes wide.  Everything that does
     // not depend on the accumulator block is computed once per wave.
     constexpr int EP = 40;                       // halves per LDS row: 32 pixels + pad (80 bytes)
     u16_alias *el = reinterpret_cast<u16_alias *>(lds) + wave * (32 * A * EP);
-    f32_alias *bw = reinterpret_cast<f32_alias *>(reinterpret_cast<u16_alias *>(lds) + NW * (32 * A * EP)) + wave * (32 * A);
-    // the wave's 32*A bias values go through LDS: one load per row instead of one per register
-#pragma unroll
-    for (int r = 0; r < (32 * A + 63) / 64; ++r) {
-        const int row = lane + 64 * r;
-        const int ml = m0 + wm * (32 * A) + row;
-        const float bvl = (p.bias && ml < Mg) ? (float)__builtin_bit_cast(_Float16, p.b[g * Mg + ml]) : 0.0f;
-        if (row < 32 * A) bw[row] = bvl;
-    }
-    typedef float __attribute__((ext_vector_type(4), may_alias)) floatx4;
-    asm volatile("" ::: "memory");
-    floatx4 bv[A][4];                            // rows 32i + 8q + 4lh + (0..3)
-#pragma unroll
-    for (int i = 0; i < A; ++i)
-#pragma unroll
-        for (int q = 0; q < 4; ++q) bv[i][q] = *reinterpret_cast<const floatx4 *>(bw + 32 * i + 8 * q + 4 * lh);
-    const float floor_v = p.relu ? 0.0f : -__builtin_inff();
+    typedef _Float16 half2v __attribute__((ext_vector_type(2)));
+    typedef float float2v __attribute__((ext_vector_type(2)));
+    const _Float16 floor_h = p.relu ? (_Float16)0.0f : (_Float16)(-__builtin_inff());
+    const half2v floor2 = {floor_h, floor_h};
     u16_alias *elw = el + (4 * lh) * EP + l32;    // this lane's column of the transpose tile
     const int row0 = lane >> 2, chunk = lane & 3;
     const u16_alias *elr = el + row0 * EP + chunk * 8;
@@ -757,9 +778,13 @@ __global__ __launch_bounds__(64 * (WAVES_M * WAVES_N + PW)) void igemm_kernel(co
 #pragma unroll
         for (int i = 0; i < A; ++i)
 #pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                const float v = fmaxf(acc[i][j][e] + bv[i][e >> 2][e & 3], floor_v);
-                elw[(i * 32 + 8 * (e >> 2) + (e & 3)) * EP] = __builtin_bit_cast(uint16_t, (_Float16)v);
+            for (int e = 0; e < 16; e += 2) {
+                // two rows at a time: one packed conversion (RNE) and one packed max
+                const float2v v = {acc[i][j][e], acc[i][j][e + 1]};
+                const half2v h = __builtin_elementwise_max(__builtin_convertvector(v, half2v), floor2);
+                const uint32_t bits = __builtin_bit_cast(uint32_t, h);
+                elw[(i * 32 + 8 * (e >> 2) + (e & 3)) * EP] = (uint16_t)bits;
+                elw[(i * 32 + 8 * (e >> 2) + (e & 3) + 1) * EP] = (uint16_t)(bits >> 16);
             }
         asm volatile("" ::: "memory");          // the reads below see the writes above
         const int pix0 = (wn * B + j) * 32 + chunk * 8;
