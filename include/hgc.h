@@ -71,6 +71,8 @@ typedef int32_t hgc_status;
 #define HGC_PATH_IGEMM_SPLITK 3  /* the same with the reduction split over workgroups;
                                     FP32 partial sums in the workspace + a reduce kernel */
 #define HGC_PATH_DEPTHWISE  4    /* group == C == num_output streaming kernel           */
+#define HGC_PATH_FIRST_LAYER 5   /* C <= 4, one group, kernel 3/5/7, packed weights: MFMA
+                                    with horizontal tap pairs folded into the reduction  */
 
 /* What a call will do for a descriptor; filled by hgc_conv2d_plan. */
 typedef struct hgc_plan {

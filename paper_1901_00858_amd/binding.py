@@ -15,7 +15,8 @@ _LIB_PATH = os.path.join(_PKG, "libhgc.so")
 _lib = None
 
 PATH_AUTO, PATH_DIRECT, PATH_IGEMM, PATH_IGEMM_SPLITK, PATH_DEPTHWISE = 0, 1, 2, 3, 4
-PATH_NAMES = {1: "direct", 2: "igemm", 3: "igemm_splitk", 4: "depthwise"}
+PATH_FIRST_LAYER = 5
+PATH_NAMES = {1: "direct", 2: "igemm", 3: "igemm_splitk", 4: "depthwise", 5: "first_layer"}
 
 
 class HgcError(RuntimeError):

@@ -114,6 +114,7 @@ struct Plan {
     ConvArgs args;
     const IgemmVariant *variant;
     double cycles;       // the cost model's estimate (implicit-GEMM paths)
+    int first_a, first_xv;   // first-layer kernel: 32-row blocks per workgroup, input pixels per load
 };
 
 static void base_args(const Geometry &g, ConvArgs *a)
@@ -321,10 +322,12 @@ static void make_plan(const Geometry &g0, bool with_ws, int x_align, bool w_al16
     const bool use_tuned = tuned && forced == HGC_PATH_AUTO && !fc.any();
     if (use_tuned) fc = *tuned;
     const bool depthwise_ok = (g.G == g.C && g.M == g.C && (g.k == 3 || g.k == 5));
+    const bool first_ok = packed && g.G == 1 && g.C <= 4 && (g.k == 3 || g.k == 5 || g.k == 7) && g.M >= 16;
 
     int path = forced;
     if (path == HGC_PATH_AUTO) {
         if (depthwise_ok) path = HGC_PATH_DEPTHWISE;
+        else if (first_ok) path = HGC_PATH_FIRST_LAYER;
         else if (g.Mg >= 16) path = HGC_PATH_IGEMM;
         else path = HGC_PATH_DIRECT;
     }
@@ -333,6 +336,40 @@ static void make_plan(const Geometry &g0, bool with_ws, int x_align, bool w_al16
         pl->pub.block = 256;
         pl->pub.grid = (int)std::min<long long>(1048576, (long long)g.N * g.C * ceil_div(g.Ho * g.Wo, 256));
         return;
+    }
+    if (path == HGC_PATH_FIRST_LAYER && first_ok) {
+        // 32 or 64 channels x 256 pixels per workgroup; the window that wastes the fewest pixels,
+        // then the smallest halo patch
+        ConvArgs *a = &pl->args;
+        const int A = g.M > 32 ? 2 : 1, BN = 256;
+        const int xv = (g.W % 2 == 0 && x_align % 4 == 0) ? 2 : 1;
+        long long best_cost = -1;
+        for (int j = 3; j <= 6; ++j) {
+            const int TW = 1 << j, TH = BN >> j;
+            const int tw_n = ceil_div(g.Wo, TW), th_n = ceil_div(g.Ho, TH);
+            const int PH = (TH - 1) * g.s + g.k, PW = (TW - 1) * g.s + g.k;
+            const int PWU = (PW + xv + 1) / 2 * 2;
+            const long long lds = smallc_lds_bytes(g.k, A, PH, PWU);
+            if (lds > kMaxLds) continue;
+            const long long cost = (long long)tw_n * th_n * (4LL * BN + (long long)PH * PWU);
+            if (best_cost < 0 || cost < best_cost) {
+                best_cost = cost;
+                a->log2_tw = j; a->tiles_w = tw_n; a->tiles_h = th_n; a->PH = PH; a->PWU = PWU;
+                pl->pub.lds_bytes = lds;
+            }
+        }
+        if (best_cost >= 0) {
+            a->tiles_m = ceil_div(g.M, 32 * A);
+            a->nsteps = 1; a->split_k = 1; a->steps_per_split = 1;
+            a->grid_blocks = a->tiles_m * a->tiles_w * a->tiles_h * g.N;
+            pl->first_a = A; pl->first_xv = xv;
+            pl->pub.path = HGC_PATH_FIRST_LAYER;
+            pl->pub.tile_m = 32 * A; pl->pub.tile_w = 1 << a->log2_tw; pl->pub.tile_h = BN >> a->log2_tw;
+            pl->pub.grid = a->grid_blocks; pl->pub.block = 256; pl->pub.variant = -1;
+            return;
+        }
+        base_args(g, &pl->args);
+        path = HGC_PATH_IGEMM;
     }
     if (path == HGC_PATH_IGEMM || path == HGC_PATH_IGEMM_SPLITK) {
         const bool ws = with_ws && (forced != HGC_PATH_IGEMM);
@@ -424,6 +461,10 @@ static hgc_status prepare(const hgc_conv2d_desc *desc, const void *x, const void
         a.wp_zero = (uint32_t)lay.zero_off;
         a.MB8 = lay.MB8;
         a.NP8 = lay.NP8;
+        if (pl.pub.path == HGC_PATH_FIRST_LAYER) {
+            a.wp_off = (uint32_t)lay.c4_off;
+            a.MB8 = lay.c4_mpad;
+        }
     }
     {   // widest output store: divides Wo and the window width, and y's byte alignment allows it
         int ov = 8;
@@ -441,6 +482,9 @@ static hipError_t enqueue(const Plan &pl, hipStream_t s)
     switch (pl.pub.path) {
     case HGC_PATH_DEPTHWISE:
         e = launch_depthwise(a, s);
+        break;
+    case HGC_PATH_FIRST_LAYER:
+        e = launch_smallc(a, pl.first_a, pl.first_xv, (size_t)pl.pub.lds_bytes, s);
         break;
     case HGC_PATH_IGEMM:
     case HGC_PATH_IGEMM_SPLITK:
@@ -613,7 +657,7 @@ hgc_status hgc_conv2d_plan(const hgc_conv2d_desc *desc, int32_t with_workspace, 
 
 int32_t hgc_set_forced_path(int32_t path, int32_t tile_variant)
 {
-    if (path < HGC_PATH_AUTO || path > HGC_PATH_DEPTHWISE) path = HGC_PATH_AUTO;
+    if (path < HGC_PATH_AUTO || path > HGC_PATH_FIRST_LAYER) path = HGC_PATH_AUTO;
     g_forced_variant.store(tile_variant, std::memory_order_relaxed);
     const int32_t before = g_forced_path.exchange(path, std::memory_order_relaxed);
     g_plan_epoch.fetch_add(1, std::memory_order_release);

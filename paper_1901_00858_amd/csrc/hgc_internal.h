@@ -93,10 +93,15 @@ const IgemmVariant *igemm_variants_packed(int *count);
 // Layout of a packed weight buffer (all offsets in bytes, multiples of 256):
 // [0, raw) the caller's weights verbatim, [igemm_off, zero_off) 16-byte units
 // [G][ceil(Mg/8)][ceil(Cg/8)][k*k][8 rows] of 8 channels, zero filled past Mg and Cg,
-// [zero_off, total) a page of zeros.
+// [zero_off, zero_off + 1024) a page of zeros, then the first-layer section if there is one.
 struct PackedLayout {
     long long raw_bytes, igemm_off, zero_off, total;
     int MB8, NP8;
+    // first-layer section (one group, at most 4 input channels, k in {3, 5, 7}; else c4_off = 0):
+    // 16-byte units [k rows][ceil(k/2) tap pairs][c4_mpad output channels] of
+    // {tap 2qp: channels 0..3, tap 2qp+1: channels 0..3}, zero past C, k and M
+    long long c4_off;
+    int c4_mpad;
 };
 PackedLayout packed_layout(const Geometry &g);
 hipError_t launch_pack_weights(const Geometry &g, const PackedLayout &pl, const uint16_t *w, uint8_t *packed,
@@ -108,5 +113,10 @@ void set_last_hip_error(hipError_t e);
 hipError_t launch_direct(const ConvArgs &a, hipStream_t stream);
 hipError_t launch_depthwise(const ConvArgs &a, hipStream_t stream);
 hipError_t launch_splitk_reduce(const ConvArgs &a, hipStream_t stream);
+// first-layer kernel (smallc.hip): blocks_m = 32-row blocks of output channels per workgroup (1 or 2),
+// xv = input pixels per load (2 or 1); a.wp_off = byte offset of the first-layer section, a.MB8 = c4_mpad,
+// a.PWU = pixels per patch row (even)
+long long smallc_lds_bytes(int ks, int blocks_m, int PH, int PWU);
+hipError_t launch_smallc(const ConvArgs &a, int blocks_m, int xv, size_t lds, hipStream_t stream);
 
 }  // namespace hgc

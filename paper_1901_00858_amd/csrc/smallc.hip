@@ -1,0 +1,217 @@
+// First-layer convolutions (at most 4 input channels, one group) on FP16 MFMA for gfx950.
+//
+// With C = 3 the general kernel pads the channels of every tap to 16 for one MFMA and
+// wastes four fifths of its loads and MFMAs.  Here the taps are folded into the reduction
+// instead: the reduction index of one MFMA (16 values) is two pairs of horizontally adjacent
+// taps x 4 channels.  The input halo patch is staged in LDS with 8-byte units = the 4
+// channels of one pixel, so the operand of a tap pair (r, 2*qp), (r, 2*qp+1) for a pixel is
+// the 16 bytes of two adjacent patch pixels: one read, whatever the stride.  The weights come
+// from the packed buffer's first-layer section (pack.hip): 16-byte units [tap row r][pair
+// qp][output channel] = {tap 2qp: c0..c3, tap 2qp+1: c0..c3}, zero past C, k and M.  The
+// whole reduction (k*ceil(k/2) units of 8) fits LDS at once, so there is no K loop: stage,
+// one barrier, MFMAs, epilogue.  Same arithmetic as everywhere: FP16 products, FP32
+// accumulation starting from the bias, one rounding (paper Sections 3.1 and 3.3).
+#include <atomic>
+
+#include "hgc_internal.h"
+#include "tile_store.h"
+
+namespace hgc {
+
+typedef uint32_t u32x2s __attribute__((ext_vector_type(2)));
+typedef u32x2s __attribute__((may_alias)) u32x2_alias;
+
+// KS: kernel extent.  A: 32-row blocks of output channels (BM = 32*A), B: 32-pixel blocks per
+// wave; 4 waves along the pixels (BN = 128*B).  XV: input pixels per global load (2 or 1).
+template <int KS, int A, int B, int XV>
+__global__ __launch_bounds__(256) void smallc_kernel(const ConvArgs p)
+{
+    constexpr int NW = 4;
+    constexpr int BM = 32 * A, BN = 32 * B * NW;
+    constexpr int QP = (KS + 1) / 2;             // tap pairs per kernel row
+    constexpr int NG = KS * QP;                  // 8-value units of the reduction
+    constexpr int NT2 = (NG + 1) / 2;            // MFMAs per accumulator block (two units each)
+    constexpr int NGP = 2 * NT2;
+    constexpr int BIAS_UNITS = NW * 8 * A;
+    constexpr int W_UNITS = NGP * BM;
+
+    extern __shared__ u32x4 lds_raw[];
+    u32x4 *const wl = lds_raw + BIAS_UNITS;
+    u32x2_alias *const xl = reinterpret_cast<u32x2_alias *>(wl + W_UNITS);   // 8-byte units: one pixel
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int l32 = lane & 31, lh = lane >> 5;
+    const int nblk = p.grid_blocks;
+    int bid;
+    {
+        const int per = (nblk + 7) >> 3;         // contiguous tile ranges per XCD
+        bid = (blockIdx.x & 7) * per + (blockIdx.x >> 3);
+        if (bid >= nblk) return;
+    }
+    const int tm = bid % p.tiles_m; bid /= p.tiles_m;
+    const int twi = bid % p.tiles_w; bid /= p.tiles_w;
+    const int thi = bid % p.tiles_h; bid /= p.tiles_h;
+    const int n = bid;
+    const int TW = 1 << p.log2_tw, TH = BN >> p.log2_tw;
+    const int oh0 = thi * TH, ow0 = twi * TW, m0 = tm * BM;
+    const int s = p.stride;
+    const int ih0 = oh0 * s - p.pad, iw0 = ow0 * s - p.pad;
+    const int iwa = iw0 & ~(XV - 1), cofs = iw0 - iwa;
+    const int PH = p.PH, PWU = p.PWU;            // patch rows, pixels per patch row (even)
+    const int HW = p.H * p.W;
+
+    const __amdgpu_buffer_rsrc_t rx = make_rsrc(p.x, p.x_bytes);
+    const __amdgpu_buffer_rsrc_t rw = make_rsrc(p.w, p.w_bytes);
+
+    // bias of the wave's rows, fetched early (see init below)
+    constexpr int BROWS = (BM + 63) / 64;
+    float bias_row[BROWS];
+#pragma unroll
+    for (int r = 0; r < BROWS; ++r) {
+        const int ml = m0 + lane + 64 * r;
+        bias_row[r] = (p.bias && lane + 64 * r < BM && ml < p.M) ? (float)__builtin_bit_cast(_Float16, p.b[ml]) : 0.0f;
+    }
+
+    // ---- weights: LDS-direct loads of whole 64-unit runs, already in operand order ----
+    constexpr int WROUNDS = (W_UNITS / 64 + NW - 1) / NW;
+#pragma unroll
+    for (int k = 0; k < WROUNDS; ++k) {
+        const int run = k * NW + wave;           // 64 units: BM/64... rows of one unit index (or two, BM = 32)
+        const int u = run * 64 + lane;
+        const int kg = u / BM, row = u % BM;
+        const bool real = (run * 64 < W_UNITS) && kg < NG;
+        const uint32_t vo = real ? p.wp_off + 16u * (uint32_t)(kg * p.MB8 + m0 + row) : p.wp_zero;
+        if (run * 64 < W_UNITS)
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rw, (lds_ptr_t)(wl + run * 64), 16, vo, 0, 0, 0);
+    }
+
+    // ---- input patch: XV pixels x 4 channels per item, transposed to pixel-major units ----
+    const int ipr = PWU / XV;
+    const int items = PH * ipr;
+    const uint32_t img_off = 2u * (uint32_t)(n * p.C * HW);
+    for (int id = tid; id < items; id += 256) {
+        const int ph = id / ipr, pd = id % ipr;
+        const int ih = ih0 + ph, iw = iwa + pd * XV;
+        const bool inside = ih >= 0 && ih < p.H && iw >= 0 && iw < p.W;
+        const uint32_t vo = inside ? img_off + 2u * (uint32_t)(ih * p.W + iw) : kNoLoad;
+        uint32_t d[4];
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const uint32_t vc = c < p.C ? vo : kNoLoad;
+            if (XV == 2) d[c] = __builtin_amdgcn_raw_buffer_load_b32(rx, vc, 2u * (uint32_t)(c * HW), 0);
+            else d[c] = (uint16_t)__builtin_amdgcn_raw_buffer_load_b16(rx, vc, 2u * (uint32_t)(c * HW), 0);
+        }
+        if (XV == 2) {
+            const u32x4 v = {pack_lo(d[0], d[1]), pack_lo(d[2], d[3]), pack_hi(d[0], d[1]), pack_hi(d[2], d[3])};
+            *reinterpret_cast<u32x4_alias *>(xl + ph * PWU + pd * 2) = v;       // PWU is even: 16-byte aligned
+        } else {
+            const u32x2s v = {d[0] | (d[1] << 16), d[2] | (d[3] << 16)};
+            xl[ph * PWU + pd] = v;
+        }
+    }
+
+    // ---- operand addresses ----
+    int xb[B];
+#pragma unroll
+    for (int j = 0; j < B; ++j) {
+        const int pix = (wave * B + j) * 32 + l32;
+        xb[j] = ((pix >> p.log2_tw) * s) * PWU + (pix & (TW - 1)) * s + cofs;
+    }
+    int toff[NT2];                               // this lane's tap-pair offset for MFMA t (lanes 32..63: the odd unit)
+#pragma unroll
+    for (int t = 0; t < NT2; ++t) {
+        const int k0 = 2 * t, k1 = (2 * t + 1 < NG) ? 2 * t + 1 : 0;      // a padding unit has zero weights
+        const int o0 = (k0 / QP) * PWU + 2 * (k0 % QP), o1 = (k1 / QP) * PWU + 2 * (k1 % QP);
+        toff[t] = lh ? o1 : o0;
+    }
+
+    // accumulators start from the bias: through the wave's private LDS words to the lanes that own the rows
+    floatx16 acc[A][B];
+    {
+        typedef float __attribute__((ext_vector_type(4), may_alias)) floatx4;
+        f32_alias *bw = reinterpret_cast<f32_alias *>(lds_raw) + wave * BM;
+#pragma unroll
+        for (int r = 0; r < BROWS; ++r)
+            if (lane + 64 * r < BM) bw[lane + 64 * r] = bias_row[r];
+        asm volatile("" ::: "memory");
+#pragma unroll
+        for (int i = 0; i < A; ++i) {
+            floatx4 bv[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) bv[q] = *reinterpret_cast<const floatx4 *>(bw + 32 * i + 8 * q + 4 * lh);
+#pragma unroll
+            for (int j = 0; j < B; ++j)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) acc[i][j][e] = bv[e >> 2][e & 3];
+        }
+    }
+    __builtin_amdgcn_s_waitcnt(0x0F70);           // the LDS-direct weight loads have landed
+    __syncthreads();
+
+    // ---- the whole reduction: NT2 MFMAs per accumulator block ----
+#pragma unroll
+    for (int t = 0; t < NT2; ++t) {
+        half8 af[A], bf[B];
+#pragma unroll
+        for (int i = 0; i < A; ++i) af[i] = __builtin_bit_cast(half8, wl[(2 * t + lh) * BM + i * 32 + l32]);
+#pragma unroll
+        for (int j = 0; j < B; ++j) {
+            const u32x2_alias *src = xl + xb[j] + toff[t];
+            const u32x2s lo = src[0], hi = src[1];
+            const u32x4 v = {lo.x, lo.y, hi.x, hi.y};
+            bf[j] = __builtin_bit_cast(half8, v);
+        }
+#pragma unroll
+        for (int i = 0; i < A; ++i)
+#pragma unroll
+            for (int j = 0; j < B; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af[i], bf[j], acc[i][j], 0, 0, 0);
+    }
+    mfma_drain();
+    __syncthreads();                              // the transpose tiles reuse the operand buffers
+    store_tile<A, B>(p, acc, wl, wave, 0, wave, lane, n, 0, m0, oh0, ow0);
+}
+
+template <int KS, int A, int B, int XV>
+static hipError_t launch_one(const ConvArgs &a, size_t lds, hipStream_t stream)
+{
+    static std::atomic<size_t> granted{0};
+    auto kern = smallc_kernel<KS, A, B, XV>;
+    if (lds > 64 * 1024 && lds > granted.load(std::memory_order_acquire)) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        granted.store(lds, std::memory_order_release);
+    }
+    hipLaunchKernelGGL(kern, dim3((unsigned)(((a.grid_blocks + 7) / 8) * 8)), dim3(256), lds, stream, a);
+    return hipGetLastError();
+}
+
+template <int KS>
+static hipError_t launch_ks(const ConvArgs &a, int blocks_m, int xv, size_t lds, hipStream_t s)
+{
+    if (blocks_m == 2) return xv == 2 ? launch_one<KS, 2, 2, 2>(a, lds, s) : launch_one<KS, 2, 2, 1>(a, lds, s);
+    return xv == 2 ? launch_one<KS, 1, 2, 2>(a, lds, s) : launch_one<KS, 1, 2, 1>(a, lds, s);
+}
+
+long long smallc_lds_bytes(int ks, int blocks_m, int PH, int PWU)
+{
+    const int qp = (ks + 1) / 2, ngp = 2 * ((ks * qp + 1) / 2), bm = 32 * blocks_m;
+    const long long bias = 16LL * 4 * 8 * blocks_m;
+    const long long main = 16LL * ngp * bm + 8LL * PH * PWU + 16;
+    const long long epi = 80LL * 32 * blocks_m * 4;
+    return bias + (main > epi ? main : epi);
+}
+
+hipError_t launch_smallc(const ConvArgs &a, int blocks_m, int xv, size_t lds, hipStream_t stream)
+{
+    switch (a.ks) {
+    case 3: return launch_ks<3>(a, blocks_m, xv, lds, stream);
+    case 5: return launch_ks<5>(a, blocks_m, xv, lds, stream);
+    case 7: return launch_ks<7>(a, blocks_m, xv, lds, stream);
+    default: return hipErrorInvalidValue;
+    }
+}
+
+}  // namespace hgc

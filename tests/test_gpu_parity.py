@@ -285,3 +285,73 @@ def test_packed_buffer_holds_the_weights_verbatim_and_zero_padding():
                 want[g, m // 8, c // 8, :, m % 8, c % 8] = wg[g, m, c, :]
     assert np.array_equal(units.view(np.uint16), want.view(np.uint16))
     assert not wp[off + units.size * 2:].any() and wp.size == hgc.conv2d_packed_weights_size(L)
+
+
+def test_first_layer_section_of_the_packed_buffer():
+    """C <= 4: the extra section holds units [k rows][tap pairs][64-padded rows] of two taps x 4 channels."""
+    import torch
+    L = _layer((1, 3, 12, 12, 40, 7, 2, 3, 1))
+    _, w, _ = make_tensors(L, seed=6)
+    wp = hgc.conv2d_pack_weights(L, torch.from_numpy(w).cuda()).cpu().numpy()
+    M, C, k = 40, 3, 7
+    raw_end = (w.size * 2 + 255) // 256 * 256
+    igemm_units = 1 * ((M + 7) // 8) * 1 * k * k * 8
+    zero_off = raw_end + (igemm_units * 16 + 255) // 256 * 256
+    c4_off = zero_off + 1024
+    assert not wp[zero_off:c4_off].any()
+    qpn, mpad = (k + 1) // 2, 64
+    sec = wp[c4_off:c4_off + k * qpn * mpad * 16].view(np.float16).reshape(k, qpn, mpad, 2, 4)
+    want = np.zeros_like(sec)
+    for r in range(k):
+        for q in range(k):
+            want[r, q // 2, :M, q % 2, :C] = w[:, :, r, q]
+    assert np.array_equal(sec.view(np.uint16), want.view(np.uint16))
+    assert not wp[c4_off + sec.size * 2:].any() and wp.size == hgc.conv2d_packed_weights_size(L)
+
+
+FIRST = [
+    # N  C  H   W   M  k  s  p
+    (1, 3, 224, 224, 64, 3, 1, 1),      # VGG conv1
+    (2, 3, 224, 224, 64, 7, 2, 3),      # ResNet stem
+    (2, 3, 224, 224, 32, 3, 2, 1),      # MobileNet conv1
+    (1, 1, 28, 28, 20, 5, 1, 0),        # config-1-like: one channel, 5x5, M not a multiple of 32
+    (3, 4, 17, 19, 48, 3, 1, 1),        # odd width: one-pixel loads; M = 48 (ragged second block)
+    (2, 2, 9, 40, 70, 5, 2, 2),         # three M tiles of 32.., ragged everything
+    (1, 3, 7, 7, 16, 7, 1, 3),          # kernel as large as the image
+    (2, 3, 33, 66, 64, 3, 2, 0),        # no padding, stride 2
+]
+
+
+@pytest.mark.parametrize("t", FIRST, ids=[f"f{i}" for i in range(len(FIRST))])
+def test_first_layer_kernel(oracle, t):
+    N, C, H, W, M, k, s, p = t
+    for bias, relu in ((1, 1), (0, 0)):
+        L = ConvLayer("first", N, C, H, W, M, k, s, p, 1, bias, relu)
+        plan = hgc.conv2d_plan(L, True, True).as_dict()
+        assert plan["path"] == hgc.PATH_FIRST_LAYER, plan
+        say(f"[first layer] {L} plan={plan}")
+        x, w, b = make_tensors(L, seed=40 + k)
+        y = run_layer(L, x, w, b, use_ws=True, packed=True)
+        assert_full(oracle, L, x, w, b, y, tag="first layer")
+
+
+def test_first_layer_kernel_integer_exact_and_unaligned_input(oracle):
+    import torch
+    L = ConvLayer("first", 2, 3, 20, 22, 40, 3, 1, 1, 1, 1, 0)
+    x, w, b = make_integer_tensors(L, seed=3)
+    pre, _ = oracle.conv2d_forward(L.desc(), x, w, b)
+    y = run_layer(L, x, w, b, use_ws=True, packed=True)
+    assert np.array_equal(y.astype(np.float64), pre)
+    # x at a 2-byte aligned address: the one-pixel-load form
+    x, w, b = make_tensors(L, seed=4)
+    xbuf = torch.empty(x.size + 1, dtype=torch.float16, device="cuda")
+    xbuf[1:].copy_(torch.from_numpy(x.reshape(-1)))
+    xd = xbuf[1:].view(L.N, L.C, L.H, L.W)
+    wp = hgc.conv2d_pack_weights(L, torch.from_numpy(w).cuda())
+    yd = torch.empty(L.y_shape, dtype=torch.float16, device="cuda")
+    yd.view(torch.int16).fill_(0x7E00)
+    st = hgc.forward_packed_raw(hgc.ConvDesc.make(L), xd.data_ptr(), wp.data_ptr(), torch.from_numpy(b).cuda().data_ptr(),
+                                yd.data_ptr(), 0, 0, torch.cuda.current_stream().cuda_stream)
+    assert st == 0
+    torch.cuda.synchronize()
+    assert_full(oracle, L, x, w, b, yd.cpu().numpy(), tag="first layer, unaligned x")
