@@ -289,6 +289,10 @@ static bool plan_igemm(const Geometry &g, bool with_ws, int x_align, bool w_al16
     a->tiles_m = best.tiles_m; a->PH = best.PH; a->PWU = best.PWU;
     a->nsteps = best.nsteps; a->split_k = best.split; a->steps_per_split = best.steps_per_split;
     a->grid_blocks = (int)(best.grid * best.split);
+    a->fd_tiles_m = make_fastdiv((uint32_t)a->tiles_m); a->fd_tiles_w = make_fastdiv((uint32_t)a->tiles_w);
+    a->fd_tiles_h = make_fastdiv((uint32_t)a->tiles_h); a->fd_G = make_fastdiv((uint32_t)g.G);
+    a->fd_N = make_fastdiv((uint32_t)g.N);
+    a->fd_ipr = make_fastdiv((uint32_t)(a->PWU / best.v->xvec)); a->fd_PH = make_fastdiv((uint32_t)a->PH);
     pl->variant = best.v;
     pl->pub.path = a->split_k > 1 ? HGC_PATH_IGEMM_SPLITK : HGC_PATH_IGEMM;
     pl->pub.tile_m = best.v->BM();
@@ -362,6 +366,10 @@ static void make_plan(const Geometry &g0, bool with_ws, int x_align, bool w_al16
             a->tiles_m = ceil_div(g.M, 32 * A);
             a->nsteps = 1; a->split_k = 1; a->steps_per_split = 1;
             a->grid_blocks = a->tiles_m * a->tiles_w * a->tiles_h * g.N;
+            a->fd_tiles_m = make_fastdiv((uint32_t)a->tiles_m); a->fd_tiles_w = make_fastdiv((uint32_t)a->tiles_w);
+            a->fd_tiles_h = make_fastdiv((uint32_t)a->tiles_h); a->fd_G = make_fastdiv(1u);
+            a->fd_N = make_fastdiv((uint32_t)g.N);
+            a->fd_ipr = make_fastdiv((uint32_t)(a->PWU / xv)); a->fd_PH = make_fastdiv((uint32_t)a->PH);
             pl->first_a = A; pl->first_xv = xv;
             pl->pub.path = HGC_PATH_FIRST_LAYER;
             pl->pub.tile_m = 32 * A; pl->pub.tile_w = 1 << a->log2_tw; pl->pub.tile_h = BN >> a->log2_tw;

@@ -19,6 +19,31 @@ struct Geometry {
     bool flat;           // pointwise layer presented to the kernels as 1 x (H*W) images
 };
 
+// Division of 0 <= n < 2^31 by a divisor fixed on the host, as multiply-high, add and shift
+// (round-up method: s = ceil(log2 d), m = floor(2^32 (2^s - d) / d) + 1, n / d = (mulhi(n, m) + n) >> s;
+// mulhi(n, m) < n < 2^31, so the sum stays below 2^32).  A runtime integer division costs the
+// kernels some thirty instructions each, at the head of every workgroup.
+struct FastDiv {
+    uint32_t d, m, s;
+};
+inline FastDiv make_fastdiv(uint32_t d)
+{
+    FastDiv f;
+    f.d = d;
+    f.s = 0;
+    while ((1ull << f.s) < d) ++f.s;
+    f.m = (uint32_t)(((1ull << 32) * ((1ull << f.s) - d)) / d + 1);
+    return f;
+}
+__host__ __device__ inline uint32_t fast_div(uint32_t n, const FastDiv &f)
+{
+#if defined(__HIP_DEVICE_COMPILE__)
+    return (__umulhi(n, f.m) + n) >> f.s;
+#else
+    return (uint32_t)((((unsigned long long)n * f.m) >> 32) + n) >> f.s;
+#endif
+}
+
 // Arguments of every kernel: tensors + geometry + the tiling chosen on the host.
 struct ConvArgs {
     const uint16_t *x;
@@ -42,6 +67,8 @@ struct ConvArgs {
     int MB8, NP8;        // packed weights: 8-row blocks per group, 8-channel planes per group
     int out_vec;         // output pixels per store (8, 4, 2 or 1): divides Wo and tile_w, fits y's alignment
     int grid_blocks;     // workgroups that have work (the launch pads to a multiple of 8)
+    FastDiv fd_tiles_m, fd_tiles_w, fd_tiles_h, fd_G, fd_N;   // workgroup id -> tile coordinates
+    FastDiv fd_ipr, fd_PH;                                     // staging item -> patch coordinates
     int split_k;         // reduction slices (1 = none)
     int steps_per_split; // channel blocks per slice
 };

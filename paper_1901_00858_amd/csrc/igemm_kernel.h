@@ -55,15 +55,16 @@ struct PatchItem {
 };
 
 template <int XVEC>
-__device__ __forceinline__ PatchItem decode_patch_item(int id, int total, int ipr, int PH, int PWU,
+__device__ __forceinline__ PatchItem decode_patch_item(int id, int total, const FastDiv &fd_ipr,
+                                                       const FastDiv &fd_PH, int PH, int PWU,
                                                        int ih0, int iwa, int H, int W, int HW,
                                                        uint32_t plane0_off, int dump_unit)
 {
     PatchItem it;
-    const int pd = id % ipr;
-    const int t = id / ipr;
-    const int ph = t % PH;
-    const int pl = t / PH;
+    const int t = (int)fast_div((uint32_t)id, fd_ipr);
+    const int pd = id - t * (int)fd_ipr.d;
+    const int pl = (int)fast_div((uint32_t)t, fd_PH);
+    const int ph = t - pl * PH;
     const int ih = ih0 + ph;
     const int iw = iwa + pd * XVEC;
     const bool active = id < total;
@@ -202,12 +203,16 @@ __global__ __launch_bounds__(64 * (WAVES_M * WAVES_N + PW)) void igemm_kernel(co
         bid = (blockIdx.x & 7) * per + (blockIdx.x >> 3);
         if (bid >= nblk) return;                 // padding workgroups of the last XCD rows
     }
-    const int tm = bid % p.tiles_m; bid /= p.tiles_m;
-    const int twi = bid % p.tiles_w; bid /= p.tiles_w;
-    const int thi = bid % p.tiles_h; bid /= p.tiles_h;
-    const int g = bid % p.G; bid /= p.G;
-    const int n = bid % p.N; bid /= p.N;
-    const int ksl = bid;
+    int q = (int)fast_div((uint32_t)bid, p.fd_tiles_m);
+    const int tm = bid - q * p.tiles_m; bid = q;
+    q = (int)fast_div((uint32_t)bid, p.fd_tiles_w);
+    const int twi = bid - q * p.tiles_w; bid = q;
+    q = (int)fast_div((uint32_t)bid, p.fd_tiles_h);
+    const int thi = bid - q * p.tiles_h; bid = q;
+    q = (int)fast_div((uint32_t)bid, p.fd_G);
+    const int g = bid - q * p.G; bid = q;
+    const int ksl = (int)fast_div((uint32_t)bid, p.fd_N);
+    const int n = bid - ksl * p.N;
 
     const int TW = 1 << p.log2_tw;
     const int TH = BN >> p.log2_tw;
@@ -234,7 +239,7 @@ __global__ __launch_bounds__(64 * (WAVES_M * WAVES_N + PW)) void igemm_kernel(co
     PatchItem pit[MAXR];
 #pragma unroll
     for (int r = 0; r < MAXR; ++r)
-        pit[r] = decode_patch_item<XVEC>(r * NT + (stid < 0 ? 0 : stid), total_items, ipr, PH, PWU, ih0, iwa,
+        pit[r] = decode_patch_item<XVEC>(r * NT + (stid < 0 ? 0 : stid), total_items, p.fd_ipr, p.fd_PH, PH, PWU, ih0, iwa,
                                          p.H, p.W, HW, plane0_off, dump_unit);
     typedef uint32_t XRegs[MAXR][8][(XVEC + 1) / 2];
     XRegs xreg[NSTAGE == 3 ? 2 : 1];             // NSTAGE 3: two steps of loads in flight
@@ -252,7 +257,7 @@ __global__ __launch_bounds__(64 * (WAVES_M * WAVES_N + PW)) void igemm_kernel(co
         if (rounds > MAXR) {
             const uint32_t soff = (uint32_t)(st * CB) * chan_bytes;
             for (int r = MAXR; r < rounds; ++r) {
-                PatchItem it = decode_patch_item<XVEC>(r * NT + stid, total_items, ipr, PH, PWU, ih0, iwa,
+                PatchItem it = decode_patch_item<XVEC>(r * NT + stid, total_items, p.fd_ipr, p.fd_PH, PH, PWU, ih0, iwa,
                                                        p.H, p.W, HW, plane0_off, dump_unit);
                 uint32_t d[8][(XVEC + 1) / 2];
                 load_patch_item<XVEC, CALIGN>(rx, it, st * CB, Cg, soff, chan_bytes, d);

@@ -49,10 +49,12 @@ __global__ __launch_bounds__(256) void smallc_kernel(const ConvArgs p)
         bid = (blockIdx.x & 7) * per + (blockIdx.x >> 3);
         if (bid >= nblk) return;
     }
-    const int tm = bid % p.tiles_m; bid /= p.tiles_m;
-    const int twi = bid % p.tiles_w; bid /= p.tiles_w;
-    const int thi = bid % p.tiles_h; bid /= p.tiles_h;
-    const int n = bid;
+    int q = (int)fast_div((uint32_t)bid, p.fd_tiles_m);
+    const int tm = bid - q * p.tiles_m; bid = q;
+    q = (int)fast_div((uint32_t)bid, p.fd_tiles_w);
+    const int twi = bid - q * p.tiles_w; bid = q;
+    const int n = (int)fast_div((uint32_t)bid, p.fd_tiles_h);
+    const int thi = bid - n * p.tiles_h;
     const int TW = 1 << p.log2_tw, TH = BN >> p.log2_tw;
     const int oh0 = thi * TH, ow0 = twi * TW, m0 = tm * BM;
     const int s = p.stride;
@@ -91,7 +93,7 @@ __global__ __launch_bounds__(256) void smallc_kernel(const ConvArgs p)
     const int items = PH * ipr;
     const uint32_t img_off = 2u * (uint32_t)(n * p.C * HW);
     for (int id = tid; id < items; id += 256) {
-        const int ph = id / ipr, pd = id % ipr;
+        const int ph = (int)fast_div((uint32_t)id, p.fd_ipr), pd = id - ph * ipr;
         const int ih = ih0 + ph, iw = iwa + pd * XV;
         const bool inside = ih >= 0 && ih < p.H && iw >= 0 && iw < p.W;
         const uint32_t vo = inside ? img_off + 2u * (uint32_t)(ih * p.W + iw) : kNoLoad;
