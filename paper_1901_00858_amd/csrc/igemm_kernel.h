@@ -230,41 +230,12 @@ __global__ __launch_bounds__(64 * (WAVES_M * WAVES_N + PW)) void igemm_kernel(co
     const __amdgpu_buffer_rsrc_t rx = make_rsrc(p.x, p.x_bytes);
     const __amdgpu_buffer_rsrc_t rw = make_rsrc(p.w, p.w_bytes);   // raw weights, or the whole packed buffer
 
-    // ---- staging maps (do not depend on the K step) ----
-    const int ipr = PWU / XVEC;                  // items per patch row
-    const int total_items = NPL * PH * ipr;
-    const int rounds = (total_items + NT - 1) / NT;
-    const uint32_t plane0_off = 2u * (uint32_t)((n * p.C + g * Cg) * HW);   // elements < 2^31: fits
-    const uint32_t chan_bytes = 2u * (uint32_t)HW;
-    PatchItem pit[MAXR];
-#pragma unroll
-    for (int r = 0; r < MAXR; ++r)
-        pit[r] = decode_patch_item<XVEC>(r * NT + (stid < 0 ? 0 : stid), total_items, p.fd_ipr, p.fd_PH, PH, PWU, ih0, iwa,
-                                         p.H, p.W, HW, plane0_off, dump_unit);
-    typedef uint32_t XRegs[MAXR][8][(XVEC + 1) / 2];
-    XRegs xreg[NSTAGE == 3 ? 2 : 1];             // NSTAGE 3: two steps of loads in flight
-
-    auto load_x = [&](int st, XRegs &xr) {
-        const uint32_t soff = (uint32_t)(st * CB) * chan_bytes;
-#pragma unroll
-        for (int r = 0; r < MAXR; ++r)
-            load_patch_item<XVEC, CALIGN>(rx, pit[r], st * CB, Cg, soff, chan_bytes, xr[r]);
-    };
-    auto store_x = [&](int st, u32x4 *xl, const XRegs &xr) {
-#pragma unroll
-        for (int r = 0; r < MAXR; ++r) store_patch_item<XVEC>(xl, pit[r], xr[r]);
-        // patches larger than the register capacity: remaining rounds, not pipelined
-        if (rounds > MAXR) {
-            const uint32_t soff = (uint32_t)(st * CB) * chan_bytes;
-            for (int r = MAXR; r < rounds; ++r) {
-                PatchItem it = decode_patch_item<XVEC>(r * NT + stid, total_items, p.fd_ipr, p.fd_PH, PH, PWU, ih0, iwa,
-                                                       p.H, p.W, HW, plane0_off, dump_unit);
-                uint32_t d[8][(XVEC + 1) / 2];
-                load_patch_item<XVEC, CALIGN>(rx, it, st * CB, Cg, soff, chan_bytes, d);
-                store_patch_item<XVEC>(xl, it, d);
-            }
-        }
-    };
+    // ---- K range of this workgroup ----
+    int st0 = 0, st1 = p.nsteps;
+    if (SPLITK) {
+        st0 = ksl * p.steps_per_split;
+        st1 = min(p.nsteps, st0 + p.steps_per_split);
+    }
 
     // ---- weights ----
     const uint32_t wgrp_off = 2u * (uint32_t)(g * Mg * Cg * T);           // M*Kg < 2^31: fits
@@ -314,6 +285,46 @@ __global__ __launch_bounds__(64 * (WAVES_M * WAVES_N + PW)) void igemm_kernel(co
 #pragma unroll
         for (int k = 0; k < WLR; ++k) load_w_round(st, wl, k);
     };
+    // the first step's weights need no index decode: get them under way before anything else
+    // (single-buffered kernels load them inside the loop, after its first barrier)
+    if (NSTAGE != 1 && (PW == 0 || wave >= NW)) load_w(st0, lds);
+
+    // ---- staging maps (do not depend on the K step) ----
+    const int ipr = PWU / XVEC;                  // items per patch row
+    const int total_items = NPL * PH * ipr;
+    const int rounds = (total_items + NT - 1) / NT;
+    const uint32_t plane0_off = 2u * (uint32_t)((n * p.C + g * Cg) * HW);   // elements < 2^31: fits
+    const uint32_t chan_bytes = 2u * (uint32_t)HW;
+    PatchItem pit[MAXR];
+#pragma unroll
+    for (int r = 0; r < MAXR; ++r)
+        pit[r] = decode_patch_item<XVEC>(r * NT + (stid < 0 ? 0 : stid), total_items, p.fd_ipr, p.fd_PH, PH, PWU, ih0, iwa,
+                                         p.H, p.W, HW, plane0_off, dump_unit);
+    typedef uint32_t XRegs[MAXR][8][(XVEC + 1) / 2];
+    XRegs xreg[NSTAGE == 3 ? 2 : 1];             // NSTAGE 3: two steps of loads in flight
+
+    auto load_x = [&](int st, XRegs &xr) {
+        const uint32_t soff = (uint32_t)(st * CB) * chan_bytes;
+#pragma unroll
+        for (int r = 0; r < MAXR; ++r)
+            load_patch_item<XVEC, CALIGN>(rx, pit[r], st * CB, Cg, soff, chan_bytes, xr[r]);
+    };
+    auto store_x = [&](int st, u32x4 *xl, const XRegs &xr) {
+#pragma unroll
+        for (int r = 0; r < MAXR; ++r) store_patch_item<XVEC>(xl, pit[r], xr[r]);
+        // patches larger than the register capacity: remaining rounds, not pipelined
+        if (rounds > MAXR) {
+            const uint32_t soff = (uint32_t)(st * CB) * chan_bytes;
+            for (int r = MAXR; r < rounds; ++r) {
+                PatchItem it = decode_patch_item<XVEC>(r * NT + stid, total_items, p.fd_ipr, p.fd_PH, PH, PWU, ih0, iwa,
+                                                       p.H, p.W, HW, plane0_off, dump_unit);
+                uint32_t d[8][(XVEC + 1) / 2];
+                load_patch_item<XVEC, CALIGN>(rx, it, st * CB, Cg, soff, chan_bytes, d);
+                store_patch_item<XVEC>(xl, it, d);
+            }
+        }
+    };
+
     // regroup items: lanes past the item count redo item (lane % WIT) and write the dump unit
     auto store_w = [&](int st, u32x4 *wl, u32x4 *xl) {
         u32x4 *mine = wl + sw * WSL;             // this wave's slice: final layout [T][NPL][RPW]
@@ -521,11 +532,6 @@ __global__ __launch_bounds__(64 * (WAVES_M * WAVES_N + PW)) void igemm_kernel(co
     typedef std::integral_constant<int, 2> all_loads;
 
     // ---- K loop over channel blocks ----
-    int st0 = 0, st1 = p.nsteps;
-    if (SPLITK) {
-        st0 = ksl * p.steps_per_split;
-        st1 = min(p.nsteps, st0 + p.steps_per_split);
-    }
     // all outstanding vector-memory operations (patch loads and LDS-direct weight rows)
     auto wait_vmem = [&]() { __builtin_amdgcn_s_waitcnt(0x0F70); };
     if constexpr (PW > 0) {
@@ -558,7 +564,6 @@ __global__ __launch_bounds__(64 * (WAVES_M * WAVES_N + PW)) void igemm_kernel(co
                 lds_barrier();
             };
             load_x(st0, xreg[0]);
-            load_w(st0, lds);
             if (st0 + 1 < st1) {
                 load_x(st0 + 1, xreg[1]);
                 load_w(st0 + 1, lds + W_UNITS);
@@ -616,7 +621,6 @@ __global__ __launch_bounds__(64 * (WAVES_M * WAVES_N + PW)) void igemm_kernel(co
             lds_barrier();
         };
         load_x(st0, xreg[0]);
-        load_w(st0, lds);
         if (st0 + 1 < st1) {
             load_x(st0 + 1, xreg[1]);
             load_w(st0 + 1, lds + W_UNITS);
@@ -640,7 +644,6 @@ __global__ __launch_bounds__(64 * (WAVES_M * WAVES_N + PW)) void igemm_kernel(co
         }
     } else if constexpr (NSTAGE == 2) {
         load_x(st0, xreg[0]);
-        load_w(st0, lds);
         wait_vmem();
         store_x(st0, lds + W_UNITS, xreg[0]);
         store_w(st0, lds, lds + W_UNITS);
