@@ -79,15 +79,17 @@ typedef struct hgc_plan {
     int32_t path;            /* HGC_PATH_*                                              */
     int32_t Ho, Wo;          /* output extent                                           */
     int32_t tile_m;          /* output channels per workgroup                           */
-    int32_t tile_h, tile_w;  /* output pixels per workgroup: tile_h rows x tile_w cols
-                                (1x1 stride-1 unpadded layers: of the image seen as one
-                                row of H*W pixels)                                      */
+    int32_t tile_h, tile_w;  /* output pixels per workgroup and image: tile_h rows x tile_w
+                                cols (1x1 stride-1 unpadded layers: of the image seen as
+                                one row of H*W pixels)                                  */
     int32_t split_k;         /* >= 1; number of reduction slices                        */
     int32_t variant;         /* kernel instantiation index (diagnostic)                 */
     int32_t grid;            /* workgroups of the main kernel                           */
     int32_t block;           /* threads per workgroup                                   */
     int64_t workspace_bytes; /* scratch the path needs (0 unless split_k > 1)           */
     int64_t lds_bytes;       /* LDS per workgroup                                       */
+    int32_t tile_n;          /* images per workgroup (small feature maps share a tile)  */
+    int32_t reserved;
 } hgc_plan;
 
 /*
@@ -168,14 +170,14 @@ hgc_status hgc_conv2d_tune(const hgc_conv2d_desc *desc, const void *x, const voi
 void hgc_conv2d_tune_reset(void);
 
 /*
- * Restores a launch shape found earlier (hgc_plan.variant, log2 of hgc_plan.tile_w,
- * hgc_plan.split_k as reported by hgc_conv2d_tune), so that a process need not measure
+ * Restores a launch shape found earlier (hgc_plan.variant, log2 of hgc_plan.tile_w, log2 of
+ * hgc_plan.tile_n, hgc_plan.split_k as reported by hgc_conv2d_tune), so that a process need not measure
  * again: remembered for calls with 16-byte aligned tensors like a shape that
  * hgc_conv2d_tune found.  Host-only.  HGC_ERR_BAD_DESC if the descriptor is invalid or the
  * shape is not one of its implicit-GEMM launch shapes.
  */
 hgc_status hgc_conv2d_set_launch_shape(const hgc_conv2d_desc *desc, int32_t packed, int32_t variant,
-                                       int32_t log2_tile_w, int32_t split_k);
+                                       int32_t log2_tile_w, int32_t log2_tile_n, int32_t split_k);
 
 /*
  * Test/diagnostic control: force one algorithm (HGC_PATH_*) for every later call
@@ -188,11 +190,12 @@ int32_t hgc_set_forced_path(int32_t path, int32_t tile_variant);
 
 /*
  * Test/diagnostic control for the implicit-GEMM path: force the output window
- * width (tile_w = 2^log2_tile_w) and the number of reduction slices; -1 = automatic.
+ * width (tile_w = 2^log2_tile_w), the number of reduction slices and the images per
+ * workgroup (tile_n = 2^log2_tile_n); -1 = automatic.
  * Combinations that do not fit are ignored (the planner then finds no candidate
  * and the call falls back to HGC_PATH_DIRECT).
  */
-void hgc_set_forced_tiling(int32_t log2_tile_w, int32_t split_k);
+void hgc_set_forced_tiling(int32_t log2_tile_w, int32_t split_k, int32_t log2_tile_n);
 
 /*
  * Inner-product (fully connected) layer forward, the other layer the paper names as

@@ -68,7 +68,8 @@ class Plan(ctypes.Structure):
     """hgc_plan."""
     _fields_ = [(n, ctypes.c_int32) for n in
                 ("path", "Ho", "Wo", "tile_m", "tile_h", "tile_w", "split_k", "variant", "grid", "block")] + \
-               [("workspace_bytes", ctypes.c_int64), ("lds_bytes", ctypes.c_int64)]
+               [("workspace_bytes", ctypes.c_int64), ("lds_bytes", ctypes.c_int64),
+                ("tile_n", ctypes.c_int32), ("reserved", ctypes.c_int32)]
 
     def as_dict(self):
         d = {n: int(getattr(self, n)) for n, _ in self._fields_}
@@ -109,11 +110,12 @@ def load():
     lib.hgc_conv2d_forward_packed.restype = ctypes.c_int32
     lib.hgc_conv2d_tune.argtypes = [dp, vp, vp, vp, vp, vp, ctypes.c_size_t, ctypes.c_int32, vp, ctypes.POINTER(Plan)]
     lib.hgc_conv2d_tune.restype = ctypes.c_int32
-    lib.hgc_conv2d_set_launch_shape.argtypes = [dp, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32]
+    lib.hgc_conv2d_set_launch_shape.argtypes = [dp, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
+                                                ctypes.c_int32]
     lib.hgc_conv2d_set_launch_shape.restype = ctypes.c_int32
     lib.hgc_conv2d_tune_reset.argtypes = []
     lib.hgc_conv2d_tune_reset.restype = None
-    lib.hgc_set_forced_tiling.argtypes = [ctypes.c_int32, ctypes.c_int32]
+    lib.hgc_set_forced_tiling.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_int32]
     lib.hgc_set_forced_tiling.restype = None
     lib.hgc_inner_product_forward.argtypes = [ctypes.POINTER(InnerProductDesc), vp, vp, vp, vp, vp]
     lib.hgc_inner_product_forward.restype = ctypes.c_int32
@@ -139,8 +141,8 @@ def set_forced_path(path: int = PATH_AUTO, tile_variant: int = -1) -> int:
     return int(load().hgc_set_forced_path(int(path), int(tile_variant)))
 
 
-def set_forced_tiling(log2_tile_w: int = -1, split_k: int = -1) -> None:
-    load().hgc_set_forced_tiling(int(log2_tile_w), int(split_k))
+def set_forced_tiling(log2_tile_w: int = -1, split_k: int = -1, log2_tile_n: int = -1) -> None:
+    load().hgc_set_forced_tiling(int(log2_tile_w), int(split_k), int(log2_tile_n))
 
 
 def igemm_variant_name(variant: int, packed: bool = False) -> str:
@@ -323,10 +325,11 @@ def conv2d_tune_reset() -> None:
     load().hgc_conv2d_tune_reset()
 
 
-def conv2d_set_launch_shape(desc, packed: bool, variant: int, log2_tile_w: int, split_k: int) -> None:
+def conv2d_set_launch_shape(desc, packed: bool, variant: int, log2_tile_w: int, split_k: int,
+                            log2_tile_n: int = 0) -> None:
     d = ConvDesc.make(desc)
     st = load().hgc_conv2d_set_launch_shape(ctypes.byref(d), 1 if packed else 0, int(variant), int(log2_tile_w),
-                                            int(split_k))
+                                            int(log2_tile_n), int(split_k))
     if st != 0:
         raise HgcError(st, "hgc_conv2d_set_launch_shape")
 

@@ -22,6 +22,7 @@ static std::atomic<int> g_forced_variant{-1};
 static thread_local int g_last_hip_error = 0;
 static std::atomic<int> g_forced_log2_tw{-1};
 static std::atomic<int> g_forced_split{-1};
+static std::atomic<int> g_forced_log2_ti{-1};
 
 static constexpr long long kMaxLds = 160 * 1024;
 
@@ -30,8 +31,8 @@ void set_last_hip_error(hipError_t e) { g_last_hip_error = (int)e; }
 // A launch shape of the implicit-GEMM path fixed from outside the cost model: by the
 // test controls or by a measurement (hgc_conv2d_tune).  -1 = let the model choose.
 struct Forced {
-    int variant = -1, log2_tw = -1, split = -1;
-    bool any() const { return variant >= 0 || log2_tw >= 0 || split >= 0; }
+    int variant = -1, log2_tw = -1, split = -1, log2_ti = -1;
+    bool any() const { return variant >= 0 || log2_tw >= 0 || split >= 0 || log2_ti >= 0; }
 };
 
 // Shapes found by hgc_conv2d_tune, keyed by everything the choice depends on.
@@ -148,7 +149,7 @@ static int ceil_div(long long a, long long b) { return (int)((a + b - 1) / b); }
 // MI355X; only the ranking matters.
 struct Candidate {
     const IgemmVariant *v;
-    int log2_tw, tiles_w, tiles_h, tiles_m, PH, PWU, nsteps, split, steps_per_split;
+    int log2_tw, log2_thi, log2_ti, tiles_w, tiles_h, tiles_m, tiles_n, PH, PWU, nsteps, split, steps_per_split;
     long long lds, grid;
     double cycles;
 };
@@ -179,12 +180,12 @@ static double estimate_cycles(const Geometry &g, const Candidate &c)
     const int RPW = v.BM() / NWS, CB = 8 * v.npl;
     const bool wdma = v.packed || v.calign;
     const int WLR = wdma ? (RPW * v.npl * T + 63) / 64 : 0, WIR = (RPW * v.npl + 63) / 64;
-    const int items = v.npl * c.PH * (c.PWU / v.xvec);
+    const int items = (v.npl * c.PH * (c.PWU / v.xvec)) << c.log2_ti;
     const int Rx = (items + NT - 1) / NT;
     const double mf_wave = 32.0 * A * B * T * v.npl / 2;
     const double wsimd_c = std::max(1.0, NW / 4.0);                     // MFMA waves per SIMD
     const double mf_simd = mf_wave * wsimd_c;
-    const double bytes_x = (double)CB * c.PH * (2.0 * c.PWU + 64.0);
+    const double bytes_x = (double)(1 << c.log2_ti) * CB * c.PH * (2.0 * c.PWU + 64.0);
     const double bytes_w = (double)v.BM() * CB * T * 2.0;
     const double TA = std::max((bytes_x + bytes_w) / 64.0, 16.0 * NWS * (8.0 * Rx + WLR));
     const double narrow = 1.0 + c_narrow * std::max(0, 5 - c.log2_tw);
@@ -252,52 +253,67 @@ static bool plan_igemm(const Geometry &g, bool with_ws, int x_align, bool w_al16
         const int BN = v.BN();
         const int f_tw = forced.log2_tw;
         const int f_sp = forced.split;
+        const int f_ti = forced.log2_ti;
         for (int j = 2; (1 << j) <= BN && j <= 9; ++j) {
             if (f_tw >= 0 && j != f_tw) continue;
-            Candidate c;
-            c.v = &v;
-            c.log2_tw = j;
-            const int TW = 1 << j, TH = BN >> j;
-            c.tiles_w = ceil_div(g.Wo, TW);
-            c.tiles_h = ceil_div(g.Ho, TH);
-            c.tiles_m = ceil_div(g.Mg, v.BM());
-            c.PH = (TH - 1) * g.s + g.k;
-            const int PW = (TW - 1) * g.s + g.k;
-            // units per patch row: PW pixels starting up to xvec-1 pixels after an aligned column
-            c.PWU = ((PW + v.xvec - 1 + v.xvec - 1) / v.xvec) * v.xvec;
-            c.lds = v.lds_bytes(c.PH, c.PWU);
-            if (c.lds > kMaxLds) continue;
-            c.nsteps = ceil_div(g.Cg, 8 * v.npl);
-            c.grid = (long long)c.tiles_m * c.tiles_w * c.tiles_h * g.G * g.N;
-            if (c.grid > (1 << 30)) continue;
-            const int max_split = (with_ws && c.nsteps >= 2) ? std::min(c.nsteps, 32) : 1;
-            for (int sp = 1; sp <= max_split; ++sp) {
-                if (sp > 4 && (sp & (sp - 1)) && sp != max_split) continue;   // 1..4, powers of two, and the maximum
-                if (force_split && sp < 2 && max_split >= 2) continue;
-                if (f_sp >= 1 && sp != std::min(f_sp, max_split)) continue;
-                c.steps_per_split = ceil_div(c.nsteps, sp);
-                c.split = ceil_div(c.nsteps, c.steps_per_split);
-                if (c.grid * c.split > (1 << 30)) continue;
-                c.cycles = estimate_cycles(g, c);
-                if (c.cycles < best.cycles) best = c;
+            // a tile may span 2^ti images: small feature maps would leave most of a tile empty
+            for (int ti = 0; ti <= 4 && (1 << (j + ti)) <= BN; ++ti) {
+                if (f_ti >= 0 && ti != f_ti) continue;
+                if (ti > 0 && (1 << ti) > g.N) break;
+                Candidate c;
+                c.v = &v;
+                c.log2_tw = j;
+                c.log2_ti = ti;
+                const int TW = 1 << j, TH = BN >> (j + ti);
+                int lth = 0;
+                while ((1 << lth) < TH) ++lth;
+                c.log2_thi = lth;
+                // more images per tile only where the map is small: at most about two windows of this size
+                if (ti > 0 && f_ti < 0 && (long long)(2 * TH) * TW <= (long long)g.Ho * g.Wo) continue;
+                c.tiles_w = ceil_div(g.Wo, TW);
+                c.tiles_h = ceil_div(g.Ho, TH);
+                c.tiles_m = ceil_div(g.Mg, v.BM());
+                c.tiles_n = ceil_div(g.N, 1 << ti);
+                c.PH = (TH - 1) * g.s + g.k;
+                const int PW = (TW - 1) * g.s + g.k;
+                // units per patch row: PW pixels starting up to xvec-1 pixels after an aligned column
+                c.PWU = ((PW + v.xvec - 1 + v.xvec - 1) / v.xvec) * v.xvec;
+                c.lds = v.lds_bytes(c.PH, c.PWU, 1 << ti);
+                if (c.lds > kMaxLds) continue;
+                c.nsteps = ceil_div(g.Cg, 8 * v.npl);
+                c.grid = (long long)c.tiles_m * c.tiles_w * c.tiles_h * g.G * c.tiles_n;
+                if (c.grid > (1 << 30)) continue;
+                const int max_split = (with_ws && c.nsteps >= 2) ? std::min(c.nsteps, 32) : 1;
+                for (int sp = 1; sp <= max_split; ++sp) {
+                    if (sp > 4 && (sp & (sp - 1)) && sp != max_split) continue;   // 1..4, powers of two, and the maximum
+                    if (force_split && sp < 2 && max_split >= 2) continue;
+                    if (f_sp >= 1 && sp != std::min(f_sp, max_split)) continue;
+                    c.steps_per_split = ceil_div(c.nsteps, sp);
+                    c.split = ceil_div(c.nsteps, c.steps_per_split);
+                    if (c.grid * c.split > (1 << 30)) continue;
+                    c.cycles = estimate_cycles(g, c);
+                    if (c.cycles < best.cycles) best = c;
+                }
             }
         }
     }
     if (!best.v) return false;
     ConvArgs *a = &pl->args;
-    a->log2_tw = best.log2_tw; a->tiles_w = best.tiles_w; a->tiles_h = best.tiles_h;
+    a->log2_tw = best.log2_tw; a->log2_thi = best.log2_thi; a->log2_ti = best.log2_ti;
+    a->tiles_n = best.tiles_n; a->tiles_w = best.tiles_w; a->tiles_h = best.tiles_h;
     a->tiles_m = best.tiles_m; a->PH = best.PH; a->PWU = best.PWU;
     a->nsteps = best.nsteps; a->split_k = best.split; a->steps_per_split = best.steps_per_split;
     a->grid_blocks = (int)(best.grid * best.split);
     a->fd_tiles_m = make_fastdiv((uint32_t)a->tiles_m); a->fd_tiles_w = make_fastdiv((uint32_t)a->tiles_w);
     a->fd_tiles_h = make_fastdiv((uint32_t)a->tiles_h); a->fd_G = make_fastdiv((uint32_t)g.G);
-    a->fd_N = make_fastdiv((uint32_t)g.N);
+    a->fd_tiles_n = make_fastdiv((uint32_t)a->tiles_n);
     a->fd_ipr = make_fastdiv((uint32_t)(a->PWU / best.v->xvec)); a->fd_PH = make_fastdiv((uint32_t)a->PH);
     pl->variant = best.v;
     pl->pub.path = a->split_k > 1 ? HGC_PATH_IGEMM_SPLITK : HGC_PATH_IGEMM;
     pl->pub.tile_m = best.v->BM();
     pl->pub.tile_w = 1 << a->log2_tw;
-    pl->pub.tile_h = best.v->BN() >> a->log2_tw;
+    pl->pub.tile_h = 1 << a->log2_thi;
+    pl->pub.tile_n = 1 << a->log2_ti;
     pl->pub.split_k = a->split_k;
     pl->pub.variant = (int)(best.v - vs);
     pl->cycles = best.cycles;
@@ -317,11 +333,13 @@ static void make_plan(const Geometry &g0, bool with_ws, int x_align, bool w_al16
     base_args(g, &pl->args);
     pl->pub.Ho = g0.Ho; pl->pub.Wo = g0.Wo;
     pl->pub.split_k = 1;
+    pl->pub.tile_n = 1;
     const int forced = g_forced_path.load(std::memory_order_relaxed);
     Forced fc;
     fc.variant = g_forced_variant.load(std::memory_order_relaxed);
     fc.log2_tw = g_forced_log2_tw.load(std::memory_order_relaxed);
     fc.split = g_forced_split.load(std::memory_order_relaxed);
+    fc.log2_ti = g_forced_log2_ti.load(std::memory_order_relaxed);
     // a measured shape applies only while no test control is active
     const bool use_tuned = tuned && forced == HGC_PATH_AUTO && !fc.any();
     if (use_tuned) fc = *tuned;
@@ -368,11 +386,14 @@ static void make_plan(const Geometry &g0, bool with_ws, int x_align, bool w_al16
             a->grid_blocks = a->tiles_m * a->tiles_w * a->tiles_h * g.N;
             a->fd_tiles_m = make_fastdiv((uint32_t)a->tiles_m); a->fd_tiles_w = make_fastdiv((uint32_t)a->tiles_w);
             a->fd_tiles_h = make_fastdiv((uint32_t)a->tiles_h); a->fd_G = make_fastdiv(1u);
-            a->fd_N = make_fastdiv((uint32_t)g.N);
+            a->tiles_n = g.N; a->fd_tiles_n = make_fastdiv((uint32_t)g.N);
+            a->log2_ti = 0;
+            for (a->log2_thi = 0; (1 << a->log2_thi) < (BN >> a->log2_tw); ++a->log2_thi) {}
             a->fd_ipr = make_fastdiv((uint32_t)(a->PWU / xv)); a->fd_PH = make_fastdiv((uint32_t)a->PH);
             pl->first_a = A; pl->first_xv = xv;
             pl->pub.path = HGC_PATH_FIRST_LAYER;
             pl->pub.tile_m = 32 * A; pl->pub.tile_w = 1 << a->log2_tw; pl->pub.tile_h = BN >> a->log2_tw;
+            pl->pub.tile_n = 1;
             pl->pub.grid = a->grid_blocks; pl->pub.block = 256; pl->pub.variant = -1;
             return;
         }
@@ -547,13 +568,15 @@ static hgc_status tune(const hgc_conv2d_desc *desc, const void *x, const void *w
     static const int splits[] = {1, 2, 3, 4, 6, 8, 12, 16, 32};
     for (int v = 0; v < nv; ++v)
         for (int j = 2; j <= 9; ++j)
+          for (int ti = 0; ti <= 4; ++ti)
             for (int sp : splits) {
                 Cand c;
-                c.f.variant = v; c.f.log2_tw = j; c.f.split = sp;
+                c.f.variant = v; c.f.log2_tw = j; c.f.split = sp; c.f.log2_ti = ti;
                 if (prepare(desc, x, w, b, y, ws, ws_bytes, true, packed, &c.f, &c.pl) != HGC_OK) continue;
                 const hgc_plan &pp = c.pl.pub;
                 if (pp.path != HGC_PATH_IGEMM && pp.path != HGC_PATH_IGEMM_SPLITK) continue;
-                if (pp.variant != v || pp.tile_w != (1 << j) || pp.split_k != sp) continue;   // not this shape
+                if (pp.variant != v || pp.tile_w != (1 << j) || pp.split_k != sp || pp.tile_n != (1 << ti))
+                    continue;                      // not this shape
                 if (c.pl.cycles > 2.5 * base.cycles) continue;
                 c.us = 0.0f;
                 cands.push_back(c);
@@ -719,19 +742,20 @@ hgc_status hgc_conv2d_tune(const hgc_conv2d_desc *desc, const void *x, const voi
 }
 
 hgc_status hgc_conv2d_set_launch_shape(const hgc_conv2d_desc *desc, int32_t packed, int32_t variant,
-                                       int32_t log2_tile_w, int32_t split_k)
+                                       int32_t log2_tile_w, int32_t log2_tile_n, int32_t split_k)
 {
     if (!desc) return HGC_ERR_NULL;
     Geometry g;
     hgc_status st = validate(desc, &g);
     if (st != HGC_OK) return st;
     Forced f;
-    f.variant = variant; f.log2_tw = log2_tile_w; f.split = split_k;
+    f.variant = variant; f.log2_tw = log2_tile_w; f.split = split_k; f.log2_ti = log2_tile_n;
     Plan pl;
     make_plan(g, true, 16, true, packed != 0, &pl, &f);
     const hgc_plan &pp = pl.pub;
     if ((pp.path != HGC_PATH_IGEMM && pp.path != HGC_PATH_IGEMM_SPLITK) || pp.variant != variant ||
-        pp.tile_w != (1 << log2_tile_w) || pp.split_k != split_k)
+        log2_tile_w < 0 || log2_tile_w > 30 || log2_tile_n < 0 || log2_tile_n > 30 ||
+        pp.tile_w != (1 << log2_tile_w) || pp.tile_n != (1 << log2_tile_n) || pp.split_k != split_k)
         return HGC_ERR_BAD_DESC;                 // not a launch shape of this descriptor
     std::lock_guard<std::mutex> lock(g_tune_mutex);
     g_tuned[tune_key(*desc, packed != 0, true, 16, true)] = f;
@@ -748,8 +772,9 @@ void hgc_conv2d_tune_reset(void)
     g_plan_epoch.fetch_add(1, std::memory_order_release);
 }
 
-void hgc_set_forced_tiling(int32_t log2_tile_w, int32_t split_k)
+void hgc_set_forced_tiling(int32_t log2_tile_w, int32_t split_k, int32_t log2_tile_n)
 {
+    g_forced_log2_ti.store(log2_tile_n, std::memory_order_relaxed);
     g_forced_log2_tw.store(log2_tile_w, std::memory_order_relaxed);
     g_forced_split.store(split_k, std::memory_order_relaxed);
     g_plan_epoch.fetch_add(1, std::memory_order_release);

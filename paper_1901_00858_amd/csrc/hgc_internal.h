@@ -56,7 +56,9 @@ struct ConvArgs {
     int ks, stride, pad;
     int bias, relu;
     // implicit-GEMM tiling
-    int log2_tw;         // tile_w = 1 << log2_tw output columns; tile_h = BN >> log2_tw rows
+    int log2_tw;         // a tile is 2^log2_ti images x 2^log2_thi rows x 2^log2_tw columns = BN pixels
+    int log2_thi, log2_ti;
+    int tiles_n;         // image tiles: ceil(N / 2^log2_ti)
     int tiles_w, tiles_h, tiles_m;
     int PH, PWU;         // input halo patch: rows, and 16-byte units (pixels) per row
     int nsteps;          // channel blocks of CB channels per group: ceil(Cg / CB)
@@ -67,7 +69,7 @@ struct ConvArgs {
     int MB8, NP8;        // packed weights: 8-row blocks per group, 8-channel planes per group
     int out_vec;         // output pixels per store (8, 4, 2 or 1): divides Wo and tile_w, fits y's alignment
     int grid_blocks;     // workgroups that have work (the launch pads to a multiple of 8)
-    FastDiv fd_tiles_m, fd_tiles_w, fd_tiles_h, fd_G, fd_N;   // workgroup id -> tile coordinates
+    FastDiv fd_tiles_m, fd_tiles_w, fd_tiles_h, fd_G, fd_tiles_n;   // workgroup id -> tile coordinates
     FastDiv fd_ipr, fd_PH;                                     // staging item -> patch coordinates
     int split_k;         // reduction slices (1 = none)
     int steps_per_split; // channel blocks per slice
@@ -103,9 +105,10 @@ struct IgemmVariant {
     int threads() const { return 64 * (waves_m * waves_n + prod_waves); }
     int stage_waves() const { return prod_waves ? prod_waves : waves_m * waves_n; }
     // LDS of a launch: stages of {weights, patch + 8 dump units}; the epilogue reuses it
-    long long lds_bytes(int PH, int PWU) const
+    long long lds_bytes(int PH, int PWU, int images = 1) const
     {
-        const long long wu = igemm_w_units(ks, wm_blocks, waves_m, stage_waves(), npl), xu = npl * PH * PWU + 8;
+        const long long wu = igemm_w_units(ks, wm_blocks, waves_m, stage_waves(), npl);
+        const long long xu = (long long)images * npl * PH * PWU + 8;
         // nstage 3: three weight buffers, two patch buffers (the patch waits in registers one step longer)
         const long long main = 16LL * (nstage == 3 ? 3 * wu + 2 * xu : nstage * (wu + xu));
         const long long epi = 80LL * 32 * wm_blocks * waves_m * waves_n;   // transpose tile per wave

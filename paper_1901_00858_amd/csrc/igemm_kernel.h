@@ -54,23 +54,25 @@ struct PatchItem {
     int pl8;         // first channel of the plane within a channel block (plane * 8)
 };
 
-template <int XVEC>
+template <int XVEC, int NPL>
 __device__ __forceinline__ PatchItem decode_patch_item(int id, int total, const FastDiv &fd_ipr,
                                                        const FastDiv &fd_PH, int PH, int PWU,
                                                        int ih0, int iwa, int H, int W, int HW,
-                                                       uint32_t plane0_off, int dump_unit)
+                                                       uint32_t plane0_off, int dump_unit,
+                                                       int img_elems, int imgs_left)
 {
     PatchItem it;
     const int t = (int)fast_div((uint32_t)id, fd_ipr);
     const int pd = id - t * (int)fd_ipr.d;
-    const int pl = (int)fast_div((uint32_t)t, fd_PH);
-    const int ph = t - pl * PH;
+    const int t2 = (int)fast_div((uint32_t)t, fd_PH);
+    const int ph = t - t2 * PH;
+    const int pl = t2 % NPL, img = t2 / NPL;     // NPL is a compile-time power of two or small constant
     const int ih = ih0 + ph;
     const int iw = iwa + pd * XVEC;
     const bool active = id < total;
-    const bool inside = active && ih >= 0 && ih < H && iw >= 0 && iw < W;
-    it.voff = inside ? plane0_off + 2u * (uint32_t)(pl * 8 * HW + ih * W + iw) : kNoLoad;
-    it.unit = active ? (pl * PH + ph) * PWU + pd * XVEC : dump_unit;
+    const bool inside = active && ih >= 0 && ih < H && iw >= 0 && iw < W && img < imgs_left;
+    it.voff = inside ? plane0_off + 2u * (uint32_t)(img * img_elems + pl * 8 * HW + ih * W + iw) : kNoLoad;
+    it.unit = active ? ((img * NPL + pl) * PH + ph) * PWU + pd * XVEC : dump_unit;
     it.pl8 = pl * 8;
     return it;
 }
@@ -178,7 +180,8 @@ __global__ __launch_bounds__(64 * (WAVES_M * WAVES_N + PW)) void igemm_kernel(co
     constexpr int BIAS_UNITS = NW * 8 * A;       // 32*A floats per wave
     extern __shared__ u32x4 lds_raw[];
     u32x4 *const lds = lds_raw + BIAS_UNITS;
-    const int X_UNITS = NPL * p.PH * p.PWU + 8;  // + dump units (one item's worth) for staging items past the end
+    const int IMG_UNITS = NPL * p.PH * p.PWU;    // patch of one image of the tile
+    const int X_UNITS = (IMG_UNITS << p.log2_ti) + 8;   // + dump units (one item's worth) for staging items past the end
     const int stage_units = W_UNITS + X_UNITS;   // [stage]{ W[wave]{[T][NPL][RPW]} , X[NPL][PH][PWU], dump }
     const int dump_unit = X_UNITS - 8;
 
@@ -211,12 +214,11 @@ __global__ __launch_bounds__(64 * (WAVES_M * WAVES_N + PW)) void igemm_kernel(co
     const int thi = bid - q * p.tiles_h; bid = q;
     q = (int)fast_div((uint32_t)bid, p.fd_G);
     const int g = bid - q * p.G; bid = q;
-    const int ksl = (int)fast_div((uint32_t)bid, p.fd_N);
-    const int n = bid - ksl * p.N;
+    const int ksl = (int)fast_div((uint32_t)bid, p.fd_tiles_n);
+    const int n = (bid - ksl * p.tiles_n) << p.log2_ti;      // first image of the tile
 
     const int TW = 1 << p.log2_tw;
-    const int TH = BN >> p.log2_tw;
-    const int oh0 = thi * TH, ow0 = twi * TW;
+    const int oh0 = thi << p.log2_thi, ow0 = twi * TW;
     const int m0 = tm * BM;
     const int s = p.stride;
     const int ih0 = oh0 * s - p.pad;
@@ -291,15 +293,15 @@ __global__ __launch_bounds__(64 * (WAVES_M * WAVES_N + PW)) void igemm_kernel(co
 
     // ---- staging maps (do not depend on the K step) ----
     const int ipr = PWU / XVEC;                  // items per patch row
-    const int total_items = NPL * PH * ipr;
+    const int total_items = (NPL * PH * ipr) << p.log2_ti;
     const int rounds = (total_items + NT - 1) / NT;
     const uint32_t plane0_off = 2u * (uint32_t)((n * p.C + g * Cg) * HW);   // elements < 2^31: fits
     const uint32_t chan_bytes = 2u * (uint32_t)HW;
     PatchItem pit[MAXR];
 #pragma unroll
     for (int r = 0; r < MAXR; ++r)
-        pit[r] = decode_patch_item<XVEC>(r * NT + (stid < 0 ? 0 : stid), total_items, p.fd_ipr, p.fd_PH, PH, PWU, ih0, iwa,
-                                         p.H, p.W, HW, plane0_off, dump_unit);
+        pit[r] = decode_patch_item<XVEC, NPL>(r * NT + (stid < 0 ? 0 : stid), total_items, p.fd_ipr, p.fd_PH, PH, PWU,
+                                              ih0, iwa, p.H, p.W, HW, plane0_off, dump_unit, p.C * HW, p.N - n);
     typedef uint32_t XRegs[MAXR][8][(XVEC + 1) / 2];
     XRegs xreg[NSTAGE == 3 ? 2 : 1];             // NSTAGE 3: two steps of loads in flight
 
@@ -316,8 +318,8 @@ __global__ __launch_bounds__(64 * (WAVES_M * WAVES_N + PW)) void igemm_kernel(co
         if (rounds > MAXR) {
             const uint32_t soff = (uint32_t)(st * CB) * chan_bytes;
             for (int r = MAXR; r < rounds; ++r) {
-                PatchItem it = decode_patch_item<XVEC>(r * NT + stid, total_items, p.fd_ipr, p.fd_PH, PH, PWU, ih0, iwa,
-                                                       p.H, p.W, HW, plane0_off, dump_unit);
+                PatchItem it = decode_patch_item<XVEC, NPL>(r * NT + stid, total_items, p.fd_ipr, p.fd_PH, PH, PWU, ih0,
+                                                            iwa, p.H, p.W, HW, plane0_off, dump_unit, p.C * HW, p.N - n);
                 uint32_t d[8][(XVEC + 1) / 2];
                 load_patch_item<XVEC, CALIGN>(rx, it, st * CB, Cg, soff, chan_bytes, d);
                 store_patch_item<XVEC>(xl, it, d);
@@ -403,8 +405,9 @@ __global__ __launch_bounds__(64 * (WAVES_M * WAVES_N + PW)) void igemm_kernel(co
 #pragma unroll
     for (int j = 0; j < B; ++j) {
         const int pix = (wn * B + j) * 32 + l32;
-        const int th = pix >> p.log2_tw, tw = pix & (TW - 1);
-        xb[j] = (lh * PH + th * s) * PWU + tw * s + cofs;
+        const int img = pix >> (p.log2_tw + p.log2_thi);
+        const int th = (pix >> p.log2_tw) & ((1 << p.log2_thi) - 1), tw = pix & (TW - 1);
+        xb[j] = img * IMG_UNITS + (lh * PH + th * s) * PWU + tw * s + cofs;
     }
     int ab[A];                                   // row -> (owning wave slice, row within it)
 #pragma unroll
@@ -709,9 +712,10 @@ __global__ __launch_bounds__(64 * (WAVES_M * WAVES_N + PW)) void igemm_kernel(co
 #pragma unroll
         for (int j = 0; j < B; ++j) {
             const int pix = (wn * B + j) * 32 + l32;
-            const int oh = oh0 + (pix >> p.log2_tw), ow = ow0 + (pix & (TW - 1));
-            const bool pix_ok = (oh < p.Ho) && (ow < p.Wo);
-            float *dst = p.ws + (((size_t)ksl * p.N + n) * p.M + (size_t)g * Mg) * HoWo + oh * p.Wo + ow;
+            const int img = pix >> (p.log2_tw + p.log2_thi);
+            const int oh = oh0 + ((pix >> p.log2_tw) & ((1 << p.log2_thi) - 1)), ow = ow0 + (pix & (TW - 1));
+            const bool pix_ok = (oh < p.Ho) && (ow < p.Wo) && (n + img < p.N);
+            float *dst = p.ws + (((size_t)ksl * p.N + n + img) * p.M + (size_t)g * Mg) * HoWo + oh * p.Wo + ow;
 #pragma unroll
             for (int i = 0; i < A; ++i)
 #pragma unroll

@@ -55,8 +55,8 @@ __global__ __launch_bounds__(256) void smallc_kernel(const ConvArgs p)
     const int twi = bid - q * p.tiles_w; bid = q;
     const int n = (int)fast_div((uint32_t)bid, p.fd_tiles_h);
     const int thi = bid - n * p.tiles_h;
-    const int TW = 1 << p.log2_tw, TH = BN >> p.log2_tw;
-    const int oh0 = thi * TH, ow0 = twi * TW, m0 = tm * BM;
+    const int TW = 1 << p.log2_tw;               // one image per tile: log2_ti = 0, 2^log2_thi = BN / TW rows
+    const int oh0 = thi << p.log2_thi, ow0 = twi * TW, m0 = tm * BM;
     const int s = p.stride;
     const int ih0 = oh0 * s - p.pad, iw0 = ow0 * s - p.pad;
     const int iwa = iw0 & ~(XV - 1), cofs = iw0 - iwa;

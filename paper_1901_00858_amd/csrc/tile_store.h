@@ -57,7 +57,8 @@ __device__ __forceinline__ void mfma_drain()
 // Epilogue of a wave that holds A x B accumulator blocks of 32 channel rows x 32 pixels:
 // accumulator register e of lane (l32, lh) in block (i, j) is channel row 8*(e/4) + 4*lh + e%4
 // and pixel column l32.  Rows start at m0 + wm*32*A (within group g), pixel blocks at
-// (wn*B + j)*32 of the workgroup's window (origin oh0, ow0; 2^log2_tw columns wide).
+// (wn*B + j)*32 of the workgroup's tile: 2^log2_ti images starting at image n, of each a window
+// of 2^log2_thi rows x 2^log2_tw columns with origin (oh0, ow0).
 // lds: at least 80*32*A bytes per wave, indexed by `wave`.
 template <int A, int B>
 __device__ __forceinline__ void store_tile(const ConvArgs &p, floatx16 (&acc)[A][B], u32x4 *lds, int wave, int wm,
@@ -67,6 +68,15 @@ __device__ __forceinline__ void store_tile(const ConvArgs &p, floatx16 (&acc)[A]
     const int HoWo = p.Ho * p.Wo;
     const int Mg = p.Mg;
     const int TW = 1 << p.log2_tw;
+    // pixel index of the workgroup's tile -> (image of the tile, row and column of its window)
+    const int img_shift = p.log2_tw + p.log2_thi, th_mask = (1 << p.log2_thi) - 1;
+    const size_t img_stride = (size_t)p.M * HoWo;
+    auto locate = [&](int pix, bool &ok) -> size_t {
+        const int img = pix >> img_shift;
+        const int oh = oh0 + ((pix >> p.log2_tw) & th_mask), ow = ow0 + (pix & (TW - 1));
+        ok = oh < p.Ho && ow < p.Wo && n + img < p.N;
+        return img * img_stride + (size_t)(oh * p.Wo + ow);
+    };
     // The bias is already in the accumulators.  One rounding to FP16 (two rows per packed
     // conversion), ReLU as a packed maximum; then each wave transposes its tile through LDS
     // (2-byte writes, 16-byte reads) so that a lane holds 8 consecutive pixels of one
@@ -101,9 +111,8 @@ __device__ __forceinline__ void store_tile(const ConvArgs &p, floatx16 (&acc)[A]
         asm volatile("" ::: "memory");          // the reads below see the writes above
         const int pix0 = (wn * B + j) * 32 + chunk * 8;
         if (ov == 8) {
-            const int oh = oh0 + (pix0 >> p.log2_tw), ow = ow0 + (pix0 & (TW - 1));
-            const bool ok = oh < p.Ho && ow < p.Wo;
-            uint16_t *dst = ybase + oh * p.Wo + ow;
+            bool ok;
+            uint16_t *dst = ybase + locate(pix0, ok);
 #pragma unroll
             for (int k = 0; k < 2 * A; ++k) {
                 const u32x4 v = *reinterpret_cast<const u32x4_alias *>(elr + k * 16 * EP);
@@ -114,10 +123,7 @@ __device__ __forceinline__ void store_tile(const ConvArgs &p, floatx16 (&acc)[A]
             uint16_t *dst[2];
 #pragma unroll
             for (int h = 0; h < 2; ++h) {
-                const int pix = pix0 + 4 * h;
-                const int oh = oh0 + (pix >> p.log2_tw), ow = ow0 + (pix & (TW - 1));
-                ok[h] = oh < p.Ho && ow < p.Wo;
-                dst[h] = ybase + oh * p.Wo + ow;
+                dst[h] = ybase + locate(pix0 + 4 * h, ok[h]);
             }
 #pragma unroll
             for (int k = 0; k < 2 * A; ++k) {
@@ -132,10 +138,7 @@ __device__ __forceinline__ void store_tile(const ConvArgs &p, floatx16 (&acc)[A]
             uint16_t *dst[4];
 #pragma unroll
             for (int h = 0; h < 4; ++h) {
-                const int pix = pix0 + 2 * h;
-                const int oh = oh0 + (pix >> p.log2_tw), ow = ow0 + (pix & (TW - 1));
-                ok[h] = oh < p.Ho && ow < p.Wo;
-                dst[h] = ybase + oh * p.Wo + ow;
+                dst[h] = ybase + locate(pix0 + 2 * h, ok[h]);
             }
 #pragma unroll
             for (int k = 0; k < 2 * A; ++k) {
@@ -150,10 +153,9 @@ __device__ __forceinline__ void store_tile(const ConvArgs &p, floatx16 (&acc)[A]
                 if (ml0 + 16 * k >= Mg) continue;
 #pragma unroll
                 for (int h = 0; h < 8; ++h) {
-                    const int pix = pix0 + h;
-                    const int oh = oh0 + (pix >> p.log2_tw), ow = ow0 + (pix & (TW - 1));
-                    if (oh < p.Ho && ow < p.Wo)
-                        (ybase + k * kstride)[oh * p.Wo + ow] = (uint16_t)(v[h >> 1] >> (16 * (h & 1)));
+                    bool ok;
+                    const size_t at = locate(pix0 + h, ok);
+                    if (ok) (ybase + k * kstride)[at] = (uint16_t)(v[h >> 1] >> (16 * (h & 1)));
                 }
             }
         }

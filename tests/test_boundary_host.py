@@ -37,7 +37,7 @@ def test_every_declared_symbol_is_exported(lib):
 
 def test_struct_layouts_match_header(lib):
     assert ctypes.sizeof(ConvDesc) == 44
-    assert ctypes.sizeof(hgc.Plan) == 56
+    assert ctypes.sizeof(hgc.Plan) == 64
     assert ctypes.sizeof(hgc.InnerProductDesc) == 20
 
 
@@ -136,9 +136,10 @@ def test_launch_shapes_can_be_restored_on_the_host(lib):
         model = hgc.conv2d_plan(L, True, True).as_dict()
         assert model["path"] in (hgc.PATH_IGEMM, hgc.PATH_IGEMM_SPLITK)
         d = hgc.ConvDesc.make(L)
-        assert lib.hgc_conv2d_set_launch_shape(None, 1, 0, 5, 1) == -1
-        assert lib.hgc_conv2d_set_launch_shape(ctypes.byref(d), 1, 9999, 5, 1) == -2
-        assert lib.hgc_conv2d_set_launch_shape(ctypes.byref(d), 1, model["variant"], 30, 1) == -2
+        assert lib.hgc_conv2d_set_launch_shape(None, 1, 0, 5, 0, 1) == -1
+        assert lib.hgc_conv2d_set_launch_shape(ctypes.byref(d), 1, 9999, 5, 0, 1) == -2
+        assert lib.hgc_conv2d_set_launch_shape(ctypes.byref(d), 1, model["variant"], 30, 0, 1) == -2
+        assert lib.hgc_conv2d_set_launch_shape(ctypes.byref(d), 1, model["variant"], 5, 3, 1) == -2   # N = 1: no 8-image tiles
         # another window of the same instantiation
         other = 4 if model["tile_w"] != 16 else 3
         hgc.conv2d_set_launch_shape(L, True, model["variant"], other, 1)
@@ -185,7 +186,7 @@ def test_plans_for_every_benchmark_layer(lib):
                     assert p.path in hgc.PATH_NAMES and p.grid >= 1 and p.block in (128, 256, 512)
                     assert p.lds_bytes <= 160 * 1024
                     if p.path in (hgc.PATH_IGEMM, hgc.PATH_IGEMM_SPLITK):
-                        assert p.tile_h * p.tile_w in (128, 256, 512) and p.tile_m in (32, 64, 128, 256)
+                        assert p.tile_n * p.tile_h * p.tile_w in (128, 256, 512) and p.tile_m in (32, 64, 128, 256)
                     if not ws:
                         assert p.workspace_bytes == 0 and p.split_k == 1
                     else:

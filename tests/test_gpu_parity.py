@@ -355,3 +355,42 @@ def test_first_layer_kernel_integer_exact_and_unaligned_input(oracle):
     assert st == 0
     torch.cuda.synchronize()
     assert_full(oracle, L, x, w, b, yd.cpu().numpy(), tag="first layer, unaligned x")
+
+
+MULTI = [
+    # N  C   H   W   M  k  s  p  G: small maps, image counts that do not fill the last tile
+    (5, 64, 7, 7, 96, 3, 1, 1, 1),
+    (7, 96, 7, 7, 64, 1, 1, 0, 1),
+    (3, 32, 5, 9, 40, 3, 2, 1, 1),
+    (6, 16, 14, 14, 32, 3, 1, 1, 2),
+    (9, 24, 4, 4, 48, 1, 1, 0, 1),
+    (4, 72, 7, 7, 160, 3, 1, 1, 1),
+]
+
+
+@pytest.mark.parametrize("t", MULTI, ids=[f"m{i}" for i in range(len(MULTI))])
+def test_tiles_that_span_several_images(oracle, t):
+    """Small feature maps share a workgroup tile: 2, 4 and 8 images per tile, whole and split
+    reductions, both weight layouts; the planner's own choice as well."""
+    L = _layer(t)
+    x, w, b = make_tensors(L, seed=77)
+    ran = 0
+    try:
+        for ti in (-1, 1, 2, 3):
+            for split in (False, True):
+                for packed in (False, True):
+                    hgc.set_forced_path(hgc.PATH_IGEMM_SPLITK if split else (hgc.PATH_IGEMM if ti >= 0 else hgc.PATH_AUTO))
+                    hgc.set_forced_tiling(-1, -1, ti)
+                    plan = hgc.conv2d_plan(L, True, packed).as_dict()
+                    if plan["path"] not in (hgc.PATH_IGEMM, hgc.PATH_IGEMM_SPLITK):
+                        continue
+                    if ti >= 0 and plan["tile_n"] != (1 << ti):
+                        continue
+                    say(f"[multi-image] {L} ti={ti} split={split} packed={packed} plan={plan}")
+                    y = run_layer(L, x, w, b, use_ws=True, packed=packed)
+                    assert_full(oracle, L, x, w, b, y, tag=f"tile_n={plan['tile_n']} split={plan['split_k']} packed={packed}")
+                    ran += plan["tile_n"] > 1
+    finally:
+        hgc.set_forced_tiling(-1, -1, -1)
+        hgc.set_forced_path(hgc.PATH_AUTO)
+    assert ran >= 4
