@@ -26,9 +26,9 @@ PEAK_HBM = 8.0e12             # MI355X HBM3E B/s
 TRAFFIC_BYTES_PER_LAUNCH = {
     # mean over the kernel's launches of a step: FETCH_SIZE KiB x 2.0 (copy calibration) + WRITE_SIZE KiB x 1.0
     # N=1: conv5..conv8 (three launches of grid 224, one of grid 112)
-    ("vgg16", 1, "packed", "igemm", 26): int((2.0 * (3 * 5049.7 + 8712.9) / 4 + (3 * 1696.0 + 784.0) / 4) * 1024),
+    ("vgg16", 1, "packed", "igemm", 26): int((2.0 * (3 * 5049.2 + 8712.0) / 4 + (3 * 1696.0 + 784.0) / 4) * 1024),
     # N=16: conv3, conv4 (grid 448) and conv5..conv7 (grid 256)
-    ("vgg16", 16, "packed", "igemm", 0): int((2.0 * (2 * 21229.8 + 3 * 14689.8) / 5 + (2 * 53142.3 + 3 * 29302.4) / 5) * 1024),
+    ("vgg16", 16, "packed", "igemm", 0): int((2.0 * (2 * 20905.5 + 3 * 14462.8) / 5 + (2 * 52721.3 + 3 * 29309.6) / 5) * 1024),
 }
 
 
