@@ -1,4 +1,4 @@
-"""Python face of the CPU oracle (oracle/conv2d_oracle.c).
+"""Python face of the CPU oracle (oracle/conv2d_oracle.c, inner_product_oracle.c, batch_norm_oracle.c).
 
 TEST INFRASTRUCTURE ONLY: imported by tests, by the smoke check and by the
 benchmark's cpu_baseline leg.  The product package never imports this module,
@@ -23,6 +23,7 @@ import numpy as np
 _DIR = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_DIR, "conv2d_oracle.c")
 _SRC_IP = os.path.join(_DIR, "inner_product_oracle.c")
+_SRC_BN = os.path.join(_DIR, "batch_norm_oracle.c")
 _LIB = os.path.join(_DIR, "libhgo.so")
 _lib = None
 
@@ -32,9 +33,9 @@ ABS_TOL = 1e-3
 
 def build(force: bool = False) -> str:
     """Compile the oracle with gcc (-O2 -fopenmp).  Returns the library path."""
-    newest = max(os.path.getmtime(_SRC), os.path.getmtime(_SRC_IP))
+    newest = max(os.path.getmtime(_SRC), os.path.getmtime(_SRC_IP), os.path.getmtime(_SRC_BN))
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < newest:
-        cmd = ["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-std=c11", "-o", _LIB, _SRC, _SRC_IP, "-lm"]
+        cmd = ["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-std=c11", "-o", _LIB, _SRC, _SRC_IP, _SRC_BN, "-lm"]
         subprocess.run(cmd, check=True)
     return _LIB
 
@@ -55,6 +56,10 @@ def _load():
         lib.hgo_conv2d_points.restype = ctypes.c_int
         lib.hgo_inner_product_forward.argtypes = [i32p, u16p, u16p, u16p, f64p, f64p]
         lib.hgo_inner_product_forward.restype = ctypes.c_int
+        f32p = ctypes.POINTER(ctypes.c_float)
+        lib.hgo_batch_norm_forward.argtypes = [i32p, ctypes.c_double, ctypes.c_double, u16p, f32p, f32p,
+                                               f64p, f64p, f64p, f64p]
+        lib.hgo_batch_norm_forward.restype = ctypes.c_int
         lib.hgo_num_threads.restype = ctypes.c_int
         lib.hgo_set_num_threads.argtypes = [ctypes.c_int]
         _lib = lib
@@ -162,6 +167,71 @@ def inner_product_forward(desc, x, w, b=None):
     if rc:
         raise ValueError(f"oracle rejected the descriptor (rc={rc})")
     return pre, mag
+
+
+BN_REL_TOL = 1e-3      # of |y|: the one FP16 rounding at the store is 2^-11 = 4.9e-4 of it
+BN_MAG_TOL = 2e-5      # of mag: FP32 statistics and the FP32 multiply-add, about 300 * 2^-24
+BN_ABS_TOL = 1e-7      # FP16's smallest subnormal step is 6e-8
+
+
+def batch_norm_forward(desc, x, eps=1e-5, mean=None, var=None, stat_scale=1.0, gamma=None, beta=None):
+    """Batch-norm layer (batch_norm_oracle.c): desc = (N, C, H, W, use_global_stats, scale_bias, relu).
+
+    x: FP16 [N][C][H][W]; mean/var (use_global_stats = 1) and gamma/beta (scale_bias = 1): FP32 [C].
+    Returns (pre, mag, mean, var): FP64 [N][C][H][W] twice, then the statistics used, FP64 [C].
+    """
+    lib = _load()
+    d = [int(v) for v in desc]
+    if len(d) != 7:
+        raise ValueError("desc = (N, C, H, W, use_global_stats, scale_bias, relu)")
+    N, C, H, W = d[:4]
+    if min(N, C, H, W) < 1:
+        raise ValueError("bad batch-norm descriptor")
+    x = np.asarray(x)
+    if x.size != N * C * H * W:
+        raise ValueError("tensor size does not match the descriptor")
+    dk = (ctypes.c_int32 * 7)(*d)
+    xk, xp = _u16(x)
+    f32p = ctypes.POINTER(ctypes.c_float)
+    f64p = ctypes.POINTER(ctypes.c_double)
+
+    def pair(a, b, what):
+        if a is None or b is None:
+            raise ValueError(what)
+        both = np.concatenate([np.asarray(a, dtype=np.float32).reshape(-1), np.asarray(b, dtype=np.float32).reshape(-1)])
+        if both.size != 2 * C:
+            raise ValueError(what)
+        return np.ascontiguousarray(both)
+
+    stats = pair(mean, var, "use_global_stats=1 needs mean and var of C values") if d[4] else None
+    gb = pair(gamma, beta, "scale_bias=1 needs gamma and beta of C values") if d[5] else None
+    pre = np.empty((N, C, H, W), dtype=np.float64)
+    mag = np.empty((N, C, H, W), dtype=np.float64)
+    mu = np.empty(C, dtype=np.float64)
+    vv = np.empty(C, dtype=np.float64)
+    rc = lib.hgo_batch_norm_forward(dk, float(eps), float(stat_scale), xp,
+                                    stats.ctypes.data_as(f32p) if stats is not None else f32p(),
+                                    gb.ctypes.data_as(f32p) if gb is not None else f32p(),
+                                    pre.ctypes.data_as(f64p), mag.ctypes.data_as(f64p),
+                                    mu.ctypes.data_as(f64p), vv.ctypes.data_as(f64p))
+    if rc:
+        raise ValueError(f"oracle rejected the descriptor (rc={rc})")
+    return pre, mag, mu, vv
+
+
+def check_batch_norm(y, pre, mag, relu):
+    """Compare an FP16 batch-norm result with the oracle: |y - ref| <= 1e-3 |ref| + 2e-5 mag + 1e-7.
+
+    Returns (ok, worst ratio |err|/bound, index).
+    """
+    ref = np.maximum(pre, 0.0) if relu else pre
+    bound = BN_REL_TOL * np.abs(ref) + BN_MAG_TOL * mag + BN_ABS_TOL
+    yd = np.asarray(y).astype(np.float64).reshape(ref.shape)
+    err = np.abs(yd - ref)
+    ratio = np.where(~np.isfinite(yd), np.inf, err / bound)
+    worst = int(np.argmax(ratio))
+    r = float(ratio.reshape(-1)[worst])
+    return bool(r <= 1.0), r, np.unravel_index(worst, ref.shape)
 
 
 def reference(pre: np.ndarray, mag: np.ndarray, relu: int):
