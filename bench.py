@@ -228,6 +228,47 @@ def main() -> int:
                               "frac_of_hbm_peak": nbytes / us / 1e3 / (PEAK_HBM / 1e9),
                               "algorithmic_bytes": nbytes})
 
+    # ---- batch-norm layers at the shapes of this stack's feature maps (the row after the inner product):
+    # HBM-bound, reported beside the headline, never part of `value`.  Algorithmic bytes: x read for the
+    # statistics, read again for the output, y written (6 B per value); 4 B per value with stored statistics ----
+    bn_shapes = {"vgg16": [(64, 224), (128, 112), (256, 56), (512, 28), (512, 14)],
+                 "resnet50": [(64, 112), (256, 56), (512, 28), (1024, 14), (2048, 7)],
+                 "mobilenet_v1": [(32, 112), (128, 56), (256, 28), (512, 14), (1024, 7)]}.get(args.config)
+    bn_report = None
+    if bn_shapes:
+        from workloads import normal01
+        bn_report = []
+        for C, S in bn_shapes:
+            Nb = args.batch
+            n = Nb * C * S * S
+            xh = (0.5 + 1.5 * normal01(9, 0, n)).astype(np.float16).reshape(Nb, C, S, S)
+            xd = torch.from_numpy(xh).to(dev)
+            yd = torch.empty_like(xd)
+            gd = torch.ones(C, dtype=torch.float32, device=dev)
+            bd = torch.zeros(C, dtype=torch.float32, device=dev)
+            md = torch.zeros(C, dtype=torch.float32, device=dev)
+            vd = torch.ones(C, dtype=torch.float32, device=dev)
+            row = {"C": C, "H": S, "W": S, "N": Nb}
+            for mode, glob, per in (("batch_statistics", 0, 6), ("stored_statistics", 1, 4)):
+                d = hgc.BatchNormDesc(Nb, C, S, S, glob, 1, 1, 1e-5, 1.0)
+                need = hgc.batch_norm_workspace_size(d)
+                wsb = torch.empty(need, dtype=torch.uint8, device=dev)
+                call = lambda: hgc.batch_norm_forward_raw(d, xd.data_ptr(), md.data_ptr(), vd.data_ptr(), gd.data_ptr(),
+                                                          bd.data_ptr(), yd.data_ptr(), wsb.data_ptr(), need, sh)
+                for _ in range(5):
+                    assert call() == 0
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record(stream)
+                for _ in range(20):
+                    call()
+                e1.record(stream)
+                e1.synchronize()
+                us = e0.elapsed_time(e1) * 1e3 / 20
+                row[mode] = {"us": us, "GB/s": per * n / us / 1e3, "frac_of_hbm_peak": per * n / us / 1e3 / (PEAK_HBM / 1e9),
+                             "algorithmic_bytes": per * n}
+                md.zero_(); vd.fill_(1.0)
+            bn_report.append(row)
+
     # ---- the oracle, as it stands, timed on the host cores (a reported baseline) ----
     cpu = None
     if not args.no_cpu:
@@ -264,6 +305,7 @@ def main() -> int:
             "entry": "hgc_conv2d_forward_ws", "ms_per_step": ms_other,
             "value": flops_step / (ms_other * 1e-3) / 1e12, "unit": "TFLOP/s"},
         "inner_product_layers": fc_report,
+        "batch_norm_layers": bn_report,
         "roofline": roof,
         "cpu_baseline": cpu,
     }

@@ -225,6 +225,53 @@ typedef struct hgc_inner_product_desc {
 hgc_status hgc_inner_product_forward(const hgc_inner_product_desc *desc, const void *x, const void *w,
                                      const void *b, void *y, void *stream);
 
+/*
+ * Batch-norm layer forward (BVLC Caffe's layer as the paper keeps it, Sections 2 and 5,
+ * optionally followed by Caffe's per-channel scale layer and a ReLU), the layer whose FP16
+ * accumulations Section 3.1 discusses:
+ *
+ *   mean[c] = (1/L) sum_{n,h,w} x[n][c][h][w],   L = N*H*W
+ *   var[c]  = (1/L) sum_{n,h,w} (x[n][c][h][w] - mean[c])^2            (biased)
+ *   y[n][c][h][w] = act( gamma[c] * (x[n][c][h][w] - mean[c]) / sqrt(var[c] + eps) + beta[c] )
+ *
+ * The mean is formed the way Section 3.1 describes, as the mean of the means of groups (a
+ * group is a run of at most 2048 consecutive values of one image's channel; groups are
+ * weighted by their lengths so that the result is the mean itself), and each group's squared
+ * deviations are taken from its own mean, then combined.  Accumulation is FP32 within a
+ * group and FP64 across groups, so the power-of-two scaling that Section 3.1 puts around the
+ * squares, which is exact in FP32, is not applied.  x is read twice and y written once.
+ *
+ * x, y: dense FP16 [N][C][H][W] in device memory, caller-owned; y may be x itself (in
+ * place) and must not overlap it otherwise.  Per-channel arrays are FP32 [C] in device
+ * memory (the paper keeps scalars in float, Section 3.2):
+ *   use_global_stats = 0: statistics of this batch.  mean and var are outputs and may each be
+ *     NULL; they receive the batch mean and the biased variance.
+ *   use_global_stats = 1: mean and var are inputs (required); the layer uses
+ *     stat_scale * mean[c] and stat_scale * var[c] (Caffe stores running sums and the
+ *     reciprocal of stat_scale beside them; pass 1 for plain statistics).
+ *   scale_bias = 1: gamma and beta are required; 0: they are ignored (1 and 0).
+ * workspace: device memory of at least hgc_batch_norm_workspace_size bytes, any alignment,
+ * caller-owned, free to reuse once the call's work has run.  desc: host.  Enqueues on
+ * `stream` and returns.  Errors, in this order and before any GPU work: HGC_ERR_NULL (desc,
+ * x or y NULL; a required array NULL), HGC_ERR_BAD_DESC (a dimension < 1; a flag not 0/1;
+ * eps not a positive finite number; with use_global_stats = 1, stat_scale not a positive
+ * finite number), HGC_ERR_TOO_LARGE (more than 2^31 - 1 elements), HGC_ERR_WORKSPACE; then
+ * HGC_ERR_LAUNCH.  Results are deterministic.  Bases need 2-byte alignment; 16-byte
+ * aligned bases with H*W % 8 == 0 take the widest loads.
+ */
+typedef struct hgc_batch_norm_desc {
+    int32_t N, C, H, W;
+    int32_t use_global_stats;   /* 0: statistics of this batch; 1: mean/var given            */
+    int32_t scale_bias;         /* 0 or 1: gamma/beta given                                  */
+    int32_t relu;               /* 0 or 1                                                    */
+    float   eps;                /* > 0; Caffe's default is 1e-5                              */
+    float   stat_scale;         /* use_global_stats = 1 only                                 */
+} hgc_batch_norm_desc;
+hgc_status hgc_batch_norm_workspace_size(const hgc_batch_norm_desc *desc, size_t *bytes);
+hgc_status hgc_batch_norm_forward(const hgc_batch_norm_desc *desc, const void *x, float *mean, float *var,
+                                  const float *gamma, const float *beta, void *y, void *workspace,
+                                  size_t workspace_bytes, void *stream);
+
 /* Static, NUL-terminated description of a status code. */
 const char *hgc_status_string(hgc_status status);
 

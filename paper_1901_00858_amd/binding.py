@@ -64,6 +64,21 @@ class InnerProductDesc(ctypes.Structure):
         return cls(*vals)
 
 
+class BatchNormDesc(ctypes.Structure):
+    """hgc_batch_norm_desc: seven int32 fields and two floats in host memory."""
+    _fields_ = [(n, ctypes.c_int32) for n in ("N", "C", "H", "W", "use_global_stats", "scale_bias", "relu")] + \
+               [("eps", ctypes.c_float), ("stat_scale", ctypes.c_float)]
+
+    @classmethod
+    def make(cls, desc, eps: float = 1e-5, stat_scale: float = 1.0) -> "BatchNormDesc":
+        if isinstance(desc, cls):
+            return desc
+        vals = [int(v) for v in desc]
+        if len(vals) != 7:
+            raise ValueError("desc = (N, C, H, W, use_global_stats, scale_bias, relu)")
+        return cls(*vals, float(eps), float(stat_scale))
+
+
 class Plan(ctypes.Structure):
     """hgc_plan."""
     _fields_ = [(n, ctypes.c_int32) for n in
@@ -119,6 +134,11 @@ def load():
     lib.hgc_set_forced_tiling.restype = None
     lib.hgc_inner_product_forward.argtypes = [ctypes.POINTER(InnerProductDesc), vp, vp, vp, vp, vp]
     lib.hgc_inner_product_forward.restype = ctypes.c_int32
+    bp = ctypes.POINTER(BatchNormDesc)
+    lib.hgc_batch_norm_workspace_size.argtypes = [bp, ctypes.POINTER(ctypes.c_size_t)]
+    lib.hgc_batch_norm_workspace_size.restype = ctypes.c_int32
+    lib.hgc_batch_norm_forward.argtypes = [bp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
+    lib.hgc_batch_norm_forward.restype = ctypes.c_int32
     lib.hgc_status_string.argtypes = [ctypes.c_int32]
     lib.hgc_status_string.restype = ctypes.c_char_p
     lib.hgc_version.restype = ctypes.c_int32
@@ -359,4 +379,64 @@ def inner_product_forward(desc, x, w, b=None, y=None):
                                    y.data_ptr(), torch.cuda.current_stream(x.device).cuda_stream)
     if st != 0:
         raise HgcError(st, "hgc_inner_product_forward")
+    return y
+
+
+def batch_norm_workspace_size_raw(desc: Optional[BatchNormDesc]):
+    """Returns (status, bytes)."""
+    out = ctypes.c_size_t(0)
+    dref = ctypes.byref(desc) if desc is not None else None
+    st = int(load().hgc_batch_norm_workspace_size(dref, ctypes.byref(out)))
+    return st, int(out.value)
+
+
+def batch_norm_workspace_size(desc, eps: float = 1e-5, stat_scale: float = 1.0) -> int:
+    st, n = batch_norm_workspace_size_raw(BatchNormDesc.make(desc, eps, stat_scale))
+    if st != 0:
+        raise HgcError(st, "hgc_batch_norm_workspace_size")
+    return n
+
+
+def batch_norm_forward_raw(desc: Optional[BatchNormDesc], x: int, mean: int, var: int, gamma: int, beta: int, y: int,
+                           workspace: int, workspace_bytes: int, stream: int = 0) -> int:
+    dref = ctypes.byref(desc) if desc is not None else None
+    return int(load().hgc_batch_norm_forward(dref, x or None, mean or None, var or None, gamma or None, beta or None,
+                                             y or None, workspace or None, int(workspace_bytes), stream or None))
+
+
+def batch_norm_forward(desc, x, eps: float = 1e-5, mean=None, var=None, stat_scale: float = 1.0, gamma=None, beta=None,
+                       y=None, workspace=None):
+    """hgc_batch_norm_forward: x FP16 [N][C][H][W] -> y (same shape; pass y=x for in place).
+
+    mean, var, gamma, beta: FP32 [C] device tensors.  With use_global_stats = 0, mean and var (if given)
+    receive the batch statistics.  Returns y.
+    """
+    import torch
+    d = BatchNormDesc.make(desc, eps, stat_scale)
+    shape = (d.N, d.C, d.H, d.W)
+    _check_tensor(x, "x", shape)
+    if y is None:
+        y = torch.empty(shape, dtype=torch.float16, device=x.device)
+    else:
+        _check_tensor(y, "y", shape)
+
+    def f32(t, name, required):
+        if t is None:
+            if required:
+                raise ValueError(f"{name} is required by the descriptor")
+            return 0
+        if t.dtype != torch.float32 or not t.is_cuda or not t.is_contiguous() or t.numel() != d.C:
+            raise ValueError(f"{name} must be a contiguous float32 device tensor of C elements")
+        return t.data_ptr()
+
+    pm, pv = f32(mean, "mean", d.use_global_stats == 1), f32(var, "var", d.use_global_stats == 1)
+    pg, pb = f32(gamma, "gamma", d.scale_bias == 1), f32(beta, "beta", d.scale_bias == 1)
+    need = batch_norm_workspace_size(d)
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=x.device)
+    st = batch_norm_forward_raw(d, x.data_ptr(), pm, pv, pg, pb, y.data_ptr(), workspace.data_ptr(),
+                                workspace.numel() * workspace.element_size(),
+                                torch.cuda.current_stream(x.device).cuda_stream)
+    if st != 0:
+        raise HgcError(st, "hgc_batch_norm_forward")
     return y

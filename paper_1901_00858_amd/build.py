@@ -9,7 +9,8 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libhgc.so")
-SOURCES = ["api.hip", "igemm_raw.hip", "igemm_packed.hip", "direct.hip", "pack.hip", "inner_product.hip", "smallc.hip"]
+SOURCES = ["api.hip", "igemm_raw.hip", "igemm_packed.hip", "direct.hip", "pack.hip", "inner_product.hip", "smallc.hip",
+           "batch_norm.hip"]
 HEADERS = [os.path.join(CSRC, "hgc_internal.h"), os.path.join(CSRC, "igemm_kernel.h"), os.path.join(CSRC, "tile_store.h"),
            os.path.join(ROOT, "include", "hgc.h")]
 
@@ -28,19 +29,28 @@ def stale() -> bool:
     return any(os.path.getmtime(d) > t for d in deps)
 
 
-def build_library(force: bool = True, verbose: bool = False) -> str:
-    """Compile every HIP source into paper_1901_00858_amd/libhgc.so. Returns its path."""
+def build_library(force: bool = True, verbose: bool = False, incremental: bool = False) -> str:
+    """Compile every HIP source into paper_1901_00858_amd/libhgc.so. Returns its path.
+
+    incremental: keep the object files (under _build/) and recompile only the sources that are newer
+    than theirs, or whose headers are; for work on one kernel.  The default compiles everything.
+    """
     if not force and not stale():
         return LIB
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    objdir = os.path.join(PKG, "_build") if incremental else CSRC
+    os.makedirs(objdir, exist_ok=True)
+    newest_header = max(os.path.getmtime(h) for h in HEADERS)
     objs = []
     procs = []
     for s in SOURCES:
-        obj = os.path.join(CSRC, s.replace(".hip", ".o"))
-        cmd = [hipcc, *FLAGS, "-I", os.path.join(ROOT, "include"), "-I", CSRC, "-c",
-               os.path.join(CSRC, s), "-o", obj]
-        procs.append((cmd, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))
+        obj = os.path.join(objdir, s.replace(".hip", ".o"))
         objs.append(obj)
+        src = os.path.join(CSRC, s)
+        if incremental and os.path.exists(obj) and os.path.getmtime(obj) > max(os.path.getmtime(src), newest_header):
+            continue
+        cmd = [hipcc, *FLAGS, "-I", os.path.join(ROOT, "include"), "-I", CSRC, "-c", src, "-o", obj]
+        procs.append((cmd, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))
     for cmd, p in procs:
         out, _ = p.communicate()
         out = "\n".join(l for l in out.splitlines() if "packed-fp32-ops" not in l)
@@ -50,10 +60,11 @@ def build_library(force: bool = True, verbose: bool = False) -> str:
             print(out, file=sys.stderr)
     cmd = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs]
     subprocess.run(cmd, check=True)
-    for o in objs:
-        os.remove(o)
+    if not incremental:
+        for o in objs:
+            os.remove(o)
     return LIB
 
 
 if __name__ == "__main__":
-    print(build_library(force=True, verbose=True))
+    print(build_library(force=True, verbose=True, incremental="--incremental" in sys.argv[1:]))

@@ -169,6 +169,38 @@ def test_inner_product_validates_on_the_host(lib):
     assert hgc.inner_product_forward_raw(ip(1 << 16, 1, 1 << 16, 0, 0), FAKE, FAKE, FAKE, FAKE) == -3
 
 
+def test_batch_norm_validates_on_the_host(lib):
+    """hgc_batch_norm_forward: NULL, BAD_DESC, TOO_LARGE, WORKSPACE, in that order, before any GPU work."""
+    def bn(N, C, H, W, g=0, sb=0, relu=0, eps=1e-5, ss=1.0):
+        return hgc.BatchNormDesc(N, C, H, W, g, sb, relu, eps, ss)
+    assert ctypes.sizeof(hgc.BatchNormDesc) == 36
+    good = bn(2, 16, 14, 14)
+    st, need = hgc.batch_norm_workspace_size_raw(good)
+    assert st == 0 and need >= 8 * 16 + 8 * 2 * 16                   # coefficients + one partial per plane
+    st, need_g = hgc.batch_norm_workspace_size_raw(bn(2, 16, 14, 14, g=1))
+    assert st == 0 and 8 * 16 <= need_g < need
+    st, big = hgc.batch_norm_workspace_size_raw(bn(2, 16, 100, 100))   # 10000 values a plane: 5 groups each
+    assert st == 0 and big >= 8 * 2 * 16 * 5
+    assert hgc.batch_norm_workspace_size_raw(None)[0] == -1
+    ws = (FAKE, 1 << 20)
+    assert hgc.batch_norm_forward_raw(None, FAKE, 0, 0, 0, 0, FAKE, *ws) == -1
+    assert hgc.batch_norm_forward_raw(good, 0, 0, 0, 0, 0, FAKE, *ws) == -1
+    assert hgc.batch_norm_forward_raw(good, FAKE, 0, 0, 0, 0, 0, *ws) == -1
+    assert hgc.batch_norm_forward_raw(bn(2, 16, 14, 14, g=1), FAKE, FAKE, 0, 0, 0, FAKE, *ws) == -1     # var missing
+    assert hgc.batch_norm_forward_raw(bn(2, 16, 14, 14, sb=1), FAKE, 0, 0, FAKE, 0, FAKE, *ws) == -1    # beta missing
+    assert hgc.batch_norm_forward_raw(bn(0, 16, 14, 14), 0, 0, 0, 0, 0, FAKE, *ws) == -1                # NULL wins
+    for bad in (bn(0, 1, 1, 1), bn(1, 0, 1, 1), bn(1, 1, 0, 1), bn(1, 1, 1, -3), bn(1, 1, 1, 1, g=2), bn(1, 1, 1, 1, sb=-1),
+                bn(1, 1, 1, 1, relu=2), bn(1, 1, 1, 1, eps=0.0), bn(1, 1, 1, 1, eps=-1.0), bn(1, 1, 1, 1, eps=float("nan")),
+                bn(1, 1, 1, 1, eps=float("inf"))):
+        assert hgc.batch_norm_forward_raw(bad, FAKE, 0, 0, 0, 0, FAKE, *ws) == -2
+        assert hgc.batch_norm_workspace_size_raw(bad)[0] == -2
+    assert hgc.batch_norm_forward_raw(bn(1, 1, 1, 1, g=1, ss=0.0), FAKE, FAKE, FAKE, 0, 0, FAKE, *ws) == -2
+    assert hgc.batch_norm_forward_raw(bn(1, 1, 1, 1, g=0, ss=0.0), FAKE, 0, 0, 0, 0, FAKE, FAKE, 0) == -4   # ignored without stored statistics
+    assert hgc.batch_norm_forward_raw(bn(1 << 10, 1 << 10, 1 << 6, 1 << 5), FAKE, 0, 0, 0, 0, FAKE, *ws) == -3
+    assert hgc.batch_norm_forward_raw(good, FAKE, 0, 0, 0, 0, FAKE, 0, 1 << 20) == -4
+    assert hgc.batch_norm_forward_raw(good, FAKE, 0, 0, 0, 0, FAKE, FAKE, need - 1) == -4
+
+
 def test_status_strings(lib):
     seen = {hgc.status_string(s) for s in (0, -1, -2, -3, -4, -5, -6)}
     assert len(seen) == 7 and hgc.status_string(0) == "ok"
