@@ -58,6 +58,11 @@ SHAPES = [
     # N, K, M: ragged everything (element-load path), then the vector path with tails in M and N
     (1, 1, 1), (3, 37, 5), (2, 40, 7), (5, 1000, 33), (1, 512, 64), (2, 520, 130), (4, 4096, 100),
     (7, 1024, 257), (8, 2048, 64), (9, 520, 130), (16, 256, 40), (17, 64, 3000), (64, 1024, 100),
+    # more than eight images (matrix-core path): K below, at and past a 128-value block, ragged rows and images,
+    # one, two and three passes of 32 images
+    (10, 8, 1), (12, 136, 17), (32, 128, 16), (33, 1032, 50), (70, 392, 33), (16, 4096, 256),
+    # four to eight images take that path on long layers only
+    (4, 72, 2048), (5, 264, 2100), (8, 64, 2047),
 ]
 
 
