@@ -1,4 +1,5 @@
-"""Python face of the CPU oracle (oracle/conv2d_oracle.c, inner_product_oracle.c, batch_norm_oracle.c).
+"""Python face of the CPU oracle (oracle/conv2d_oracle.c, inner_product_oracle.c, batch_norm_oracle.c,
+max_pool_oracle.c).
 
 TEST INFRASTRUCTURE ONLY: imported by tests, by the smoke check and by the
 benchmark's cpu_baseline leg.  The product package never imports this module,
@@ -24,6 +25,7 @@ _DIR = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_DIR, "conv2d_oracle.c")
 _SRC_IP = os.path.join(_DIR, "inner_product_oracle.c")
 _SRC_BN = os.path.join(_DIR, "batch_norm_oracle.c")
+_SRC_MP = os.path.join(_DIR, "max_pool_oracle.c")
 _LIB = os.path.join(_DIR, "libhgo.so")
 _lib = None
 
@@ -33,9 +35,9 @@ ABS_TOL = 1e-3
 
 def build(force: bool = False) -> str:
     """Compile the oracle with gcc (-O2 -fopenmp).  Returns the library path."""
-    newest = max(os.path.getmtime(_SRC), os.path.getmtime(_SRC_IP), os.path.getmtime(_SRC_BN))
+    newest = max(os.path.getmtime(_SRC), os.path.getmtime(_SRC_IP), os.path.getmtime(_SRC_BN), os.path.getmtime(_SRC_MP))
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < newest:
-        cmd = ["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-std=c11", "-o", _LIB, _SRC, _SRC_IP, _SRC_BN, "-lm"]
+        cmd = ["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-std=c11", "-o", _LIB, _SRC, _SRC_IP, _SRC_BN, _SRC_MP, "-lm"]
         subprocess.run(cmd, check=True)
     return _LIB
 
@@ -60,6 +62,10 @@ def _load():
         lib.hgo_batch_norm_forward.argtypes = [i32p, ctypes.c_double, ctypes.c_double, u16p, f32p, f32p,
                                                f64p, f64p, f64p, f64p]
         lib.hgo_batch_norm_forward.restype = ctypes.c_int
+        lib.hgo_max_pool_shape.argtypes = [i32p, i32p]
+        lib.hgo_max_pool_shape.restype = ctypes.c_int
+        lib.hgo_max_pool_forward.argtypes = [i32p, u16p, u16p]
+        lib.hgo_max_pool_forward.restype = ctypes.c_int
         lib.hgo_num_threads.restype = ctypes.c_int
         lib.hgo_set_num_threads.argtypes = [ctypes.c_int]
         _lib = lib
@@ -232,6 +238,31 @@ def check_batch_norm(y, pre, mag, relu):
     worst = int(np.argmax(ratio))
     r = float(ratio.reshape(-1)[worst])
     return bool(r <= 1.0), r, np.unravel_index(worst, ref.shape)
+
+
+def max_pool_shape(desc):
+    """(Ho, Wo) of Caffe's max pooling for desc = (N, C, H, W, kernel, stride, pad)."""
+    d = (ctypes.c_int32 * 7)(*[int(v) for v in desc])
+    o = (ctypes.c_int32 * 2)()
+    if len(desc) != 7 or _load().hgo_max_pool_shape(d, o):
+        raise ValueError("bad max-pool descriptor")
+    return int(o[0]), int(o[1])
+
+
+def max_pool_forward(desc, x):
+    """Max pooling (max_pool_oracle.c): x FP16 [N][C][H][W] -> FP16 [N][C][Ho][Wo], exact."""
+    ho, wo = max_pool_shape(desc)
+    N, C, H, W = [int(v) for v in desc[:4]]
+    x = np.asarray(x)
+    if x.size != N * C * H * W:
+        raise ValueError("tensor size does not match the descriptor")
+    xk, xp = _u16(x)
+    y = np.empty((N, C, ho, wo), dtype=np.float16)
+    d = (ctypes.c_int32 * 7)(*[int(v) for v in desc])
+    rc = _load().hgo_max_pool_forward(d, xp, y.view(np.uint16).ctypes.data_as(ctypes.POINTER(ctypes.c_uint16)))
+    if rc:
+        raise ValueError(f"oracle rejected the descriptor (rc={rc})")
+    return y
 
 
 def reference(pre: np.ndarray, mag: np.ndarray, relu: int):
