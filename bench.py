@@ -269,6 +269,65 @@ def main() -> int:
                 md.zero_(); vd.fill_(1.0)
             bn_report.append(row)
 
+    # ---- the whole VGG-16-shaped forward pass as one chain (the row after batch norm): the 13 convolutions of
+    # the headline stack feeding each other through five 2x2 max-poolings, then fc6, fc7, fc8; every layer
+    # reads the previous layer's output in HBM.  Reported beside the headline, never part of `value` ----
+    chain = None
+    if args.config == "vgg16" and args.entry == "packed":
+        from workloads import uniform01, normal01
+        pool_after = {1, 3, 6, 9, 12}                      # conv2, conv4, conv7, conv10, conv13
+        Nb = args.batch
+        steps_c = []                                      # (kind, descriptor, argument pointers..., output tensor)
+        cur = bufs[0][1]                                  # the first layer's own input
+        keep = []
+        for i, L in enumerate(layers):
+            d, _xd, _wd, bd, _y, ws, need, wp = bufs[i]
+            yo = torch.empty((Nb, L.M, L.H, L.W), dtype=torch.float16, device=dev)
+            steps_c.append(("conv", d, cur, wp, bd, yo, ws, need))
+            cur = yo
+            if i in pool_after:
+                pd = hgc.MaxPoolDesc(Nb, L.M, L.H, L.W, 2, 2, 0)
+                po = torch.empty((Nb, L.M, L.H // 2, L.W // 2), dtype=torch.float16, device=dev)
+                steps_c.append(("pool", pd, cur, po))
+                cur = po
+        K = cur.numel() // Nb
+        for name, M, relu in (("fc6", 4096, 1), ("fc7", 4096, 1), ("fc8", 1000, 0)):
+            wh = (normal01(8, len(keep), M * K) * np.sqrt(2.0 / K)).astype(np.float16).reshape(M, K)
+            bh = (0.2 * uniform01(8, 100 + len(keep), M) - 0.1).astype(np.float16)
+            wd2, bd2 = torch.from_numpy(wh).to(dev), torch.from_numpy(bh).to(dev)
+            keep.append((wd2, bd2))
+            yo = torch.empty((Nb, M), dtype=torch.float16, device=dev)
+            steps_c.append(("fc", hgc.InnerProductDesc(Nb, K, M, 1, relu), cur, wd2, bd2, yo))
+            cur, K = yo, M
+
+        def forward_chain():
+            for st in steps_c:
+                if st[0] == "conv":
+                    _, d, xi, wp, bd, yo, ws, need = st
+                    rc = hgc.forward_packed_raw(d, xi.data_ptr(), wp.data_ptr(), bd.data_ptr(), yo.data_ptr(),
+                                                ws.data_ptr(), need, sh)
+                elif st[0] == "pool":
+                    rc = hgc.max_pool_forward_raw(st[1], st[2].data_ptr(), st[3].data_ptr(), sh)
+                else:
+                    _, d, xi, w2, b2, yo = st
+                    rc = hgc.inner_product_forward_raw(d, xi.data_ptr(), w2.data_ptr(), b2.data_ptr(), yo.data_ptr(), sh)
+                if rc != 0:
+                    raise hgc.HgcError(rc, "chain " + st[0])
+
+        for _ in range(max(3, args.warmup // 2)):
+            forward_chain()
+        torch.cuda.synchronize()
+        csteps = max(5, args.steps // 2)
+        t0 = time.perf_counter()
+        for _ in range(csteps):
+            forward_chain()
+        torch.cuda.synchronize()
+        ms_chain = (time.perf_counter() - t0) * 1e3 / csteps
+        out_ok = bool(torch.isfinite(cur.float()).all().item())
+        chain = {"what": "VGG-16-shaped forward pass: 13 conv (bias+ReLU) + 5 max-pool 2x2/2 + fc6, fc7 (ReLU), fc8, chained in HBM",
+                 "calls_per_step": len(steps_c), "steps": csteps, "ms_per_step": ms_chain, "ms_per_image": ms_chain / Nb,
+                 "images_per_s": Nb / (ms_chain * 1e-3), "output_finite": out_ok}
+
     # ---- the oracle, as it stands, timed on the host cores (a reported baseline) ----
     cpu = None
     if not args.no_cpu:
@@ -306,6 +365,7 @@ def main() -> int:
             "value": flops_step / (ms_other * 1e-3) / 1e12, "unit": "TFLOP/s"},
         "inner_product_layers": fc_report,
         "batch_norm_layers": bn_report,
+        "full_forward": chain,
         "roofline": roof,
         "cpu_baseline": cpu,
     }

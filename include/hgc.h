@@ -272,6 +272,31 @@ hgc_status hgc_batch_norm_forward(const hgc_batch_norm_desc *desc, const void *x
                                   const float *gamma, const float *beta, void *y, void *workspace,
                                   size_t workspace_bytes, void *stream);
 
+/*
+ * Max-pooling layer forward: BVLC Caffe's MAX pooling, which sits between the convolutions of
+ * the networks the paper runs (Section 4; the paper keeps Caffe's layers, Sections 2 and 5).
+ * Square window `kernel`, stride, symmetric padding pad < kernel:
+ *
+ *   Ho = ceil((H + 2*pad - kernel) / stride) + 1, one less if pad > 0 and the last window
+ *        would start at or beyond H + pad; Wo likewise (hgc_max_pool_output_size)
+ *   y[n][c][oh][ow] = maximum of x[n][c] over the window at (oh*stride - pad, ow*stride - pad),
+ *        clipped to the image: padding never takes part, the last window may hang over the edge
+ *
+ * x [N][C][H][W], y [N][C][Ho][Wo]: dense FP16 in device memory, caller-owned, not overlapping.
+ * The result is one of the inputs, bit for bit (for +0 against -0: either); inputs are finite.
+ * desc: host.  Enqueues on `stream` and returns; no workspace.  Errors, in this order and before
+ * any GPU work: HGC_ERR_NULL, HGC_ERR_BAD_DESC (a dimension, kernel or stride < 1; pad < 0 or
+ * pad >= kernel; a padded extent smaller than the window), HGC_ERR_TOO_LARGE (more than
+ * 2^31 - 1 elements); then HGC_ERR_LAUNCH.  Bases need 2-byte alignment; the 2x2 / stride 2 /
+ * pad 0 window with W % 8 == 0, a 16-byte aligned x and an 8-byte aligned y takes vector loads.
+ */
+typedef struct hgc_max_pool_desc {
+    int32_t N, C, H, W;
+    int32_t kernel, stride, pad;
+} hgc_max_pool_desc;
+hgc_status hgc_max_pool_output_size(const hgc_max_pool_desc *desc, int32_t *Ho, int32_t *Wo);
+hgc_status hgc_max_pool_forward(const hgc_max_pool_desc *desc, const void *x, void *y, void *stream);
+
 /* Static, NUL-terminated description of a status code. */
 const char *hgc_status_string(hgc_status status);
 

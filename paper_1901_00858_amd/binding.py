@@ -79,6 +79,20 @@ class BatchNormDesc(ctypes.Structure):
         return cls(*vals, float(eps), float(stat_scale))
 
 
+class MaxPoolDesc(ctypes.Structure):
+    """hgc_max_pool_desc: seven int32 fields in host memory."""
+    _fields_ = [(n, ctypes.c_int32) for n in ("N", "C", "H", "W", "kernel", "stride", "pad")]
+
+    @classmethod
+    def make(cls, desc) -> "MaxPoolDesc":
+        if isinstance(desc, cls):
+            return desc
+        vals = [int(v) for v in desc]
+        if len(vals) != 7:
+            raise ValueError("desc = (N, C, H, W, kernel, stride, pad)")
+        return cls(*vals)
+
+
 class Plan(ctypes.Structure):
     """hgc_plan."""
     _fields_ = [(n, ctypes.c_int32) for n in
@@ -139,6 +153,11 @@ def load():
     lib.hgc_batch_norm_workspace_size.restype = ctypes.c_int32
     lib.hgc_batch_norm_forward.argtypes = [bp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
     lib.hgc_batch_norm_forward.restype = ctypes.c_int32
+    mp = ctypes.POINTER(MaxPoolDesc)
+    lib.hgc_max_pool_output_size.argtypes = [mp, ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_int32)]
+    lib.hgc_max_pool_output_size.restype = ctypes.c_int32
+    lib.hgc_max_pool_forward.argtypes = [mp, vp, vp, vp]
+    lib.hgc_max_pool_forward.restype = ctypes.c_int32
     lib.hgc_status_string.argtypes = [ctypes.c_int32]
     lib.hgc_status_string.restype = ctypes.c_char_p
     lib.hgc_version.restype = ctypes.c_int32
@@ -439,4 +458,40 @@ def batch_norm_forward(desc, x, eps: float = 1e-5, mean=None, var=None, stat_sca
                                 torch.cuda.current_stream(x.device).cuda_stream)
     if st != 0:
         raise HgcError(st, "hgc_batch_norm_forward")
+    return y
+
+
+def max_pool_output_size_raw(desc: Optional[MaxPoolDesc]):
+    """Returns (status, Ho, Wo)."""
+    ho, wo = ctypes.c_int32(0), ctypes.c_int32(0)
+    dref = ctypes.byref(desc) if desc is not None else None
+    st = int(load().hgc_max_pool_output_size(dref, ctypes.byref(ho), ctypes.byref(wo)))
+    return st, int(ho.value), int(wo.value)
+
+
+def max_pool_output_size(desc):
+    st, ho, wo = max_pool_output_size_raw(MaxPoolDesc.make(desc))
+    if st != 0:
+        raise HgcError(st, "hgc_max_pool_output_size")
+    return ho, wo
+
+
+def max_pool_forward_raw(desc: Optional[MaxPoolDesc], x: int, y: int, stream: int = 0) -> int:
+    dref = ctypes.byref(desc) if desc is not None else None
+    return int(load().hgc_max_pool_forward(dref, x or None, y or None, stream or None))
+
+
+def max_pool_forward(desc, x, y=None):
+    """hgc_max_pool_forward: x FP16 [N][C][H][W] -> y FP16 [N][C][Ho][Wo]."""
+    import torch
+    d = MaxPoolDesc.make(desc)
+    _check_tensor(x, "x", (d.N, d.C, d.H, d.W))
+    ho, wo = max_pool_output_size(d)
+    if y is None:
+        y = torch.empty((d.N, d.C, ho, wo), dtype=torch.float16, device=x.device)
+    else:
+        _check_tensor(y, "y", (d.N, d.C, ho, wo))
+    st = max_pool_forward_raw(d, x.data_ptr(), y.data_ptr(), torch.cuda.current_stream(x.device).cuda_stream)
+    if st != 0:
+        raise HgcError(st, "hgc_max_pool_forward")
     return y

@@ -201,6 +201,28 @@ def test_batch_norm_validates_on_the_host(lib):
     assert hgc.batch_norm_forward_raw(good, FAKE, 0, 0, 0, 0, FAKE, FAKE, need - 1) == -4
 
 
+def test_max_pool_validates_on_the_host(lib):
+    """hgc_max_pool_forward / hgc_max_pool_output_size: NULL, BAD_DESC, TOO_LARGE before any GPU work."""
+    mp = hgc.MaxPoolDesc
+    assert ctypes.sizeof(mp) == 28
+    assert hgc.max_pool_output_size_raw(mp(1, 64, 224, 224, 2, 2, 0)) == (0, 112, 112)
+    assert hgc.max_pool_output_size_raw(mp(1, 96, 55, 55, 3, 2, 0)) == (0, 27, 27)
+    assert hgc.max_pool_output_size_raw(mp(1, 64, 112, 112, 3, 2, 1)) == (0, 57, 57)     # rounded up
+    assert hgc.max_pool_output_size_raw(mp(1, 1, 3, 3, 2, 2, 1)) == (0, 2, 2)             # last window in the padding: dropped
+    assert hgc.max_pool_output_size_raw(None)[0] == -1
+    good = mp(2, 3, 8, 8, 2, 2, 0)
+    assert hgc.max_pool_forward_raw(None, FAKE, FAKE) == -1
+    assert hgc.max_pool_forward_raw(good, 0, FAKE) == -1
+    assert hgc.max_pool_forward_raw(good, FAKE, 0) == -1
+    assert hgc.max_pool_forward_raw(mp(0, 3, 8, 8, 2, 2, 0), 0, FAKE) == -1               # NULL wins
+    for bad in (mp(0, 3, 8, 8, 2, 2, 0), mp(1, 0, 8, 8, 2, 2, 0), mp(1, 1, 0, 8, 2, 2, 0), mp(1, 1, 8, -1, 2, 2, 0),
+                mp(1, 1, 8, 8, 0, 2, 0), mp(1, 1, 8, 8, 2, 0, 0), mp(1, 1, 8, 8, 2, 2, -1), mp(1, 1, 8, 8, 2, 2, 2),
+                mp(1, 1, 2, 8, 3, 1, 0)):
+        assert hgc.max_pool_forward_raw(bad, FAKE, FAKE) == -2
+        assert hgc.max_pool_output_size_raw(bad)[0] == -2
+    assert hgc.max_pool_forward_raw(mp(1 << 10, 1 << 10, 1 << 6, 1 << 5, 2, 2, 0), FAKE, FAKE) == -3
+
+
 def test_status_strings(lib):
     seen = {hgc.status_string(s) for s in (0, -1, -2, -3, -4, -5, -6)}
     assert len(seen) == 7 and hgc.status_string(0) == "ok"
