@@ -62,6 +62,9 @@ def _load():
         lib.hgo_batch_norm_forward.argtypes = [i32p, ctypes.c_double, ctypes.c_double, u16p, f32p, f32p,
                                                f64p, f64p, f64p, f64p]
         lib.hgo_batch_norm_forward.restype = ctypes.c_int
+        lib.hgo_batch_norm_fold.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_double, ctypes.c_double, u16p, u16p,
+                                            f32p, f32p, f64p, f64p]
+        lib.hgo_batch_norm_fold.restype = ctypes.c_int
         lib.hgo_max_pool_shape.argtypes = [i32p, i32p]
         lib.hgo_max_pool_shape.restype = ctypes.c_int
         lib.hgo_max_pool_forward.argtypes = [i32p, u16p, u16p]
@@ -223,6 +226,40 @@ def batch_norm_forward(desc, x, eps=1e-5, mean=None, var=None, stat_scale=1.0, g
     if rc:
         raise ValueError(f"oracle rejected the descriptor (rc={rc})")
     return pre, mag, mu, vv
+
+
+def batch_norm_fold(w, b, mean, var, eps=1e-5, stat_scale=1.0, gamma=None, beta=None):
+    """Stored batch-norm statistics folded into a convolution's weights and bias (batch_norm_oracle.c).
+
+    w: FP16 [M][...]; b: FP16 [M] or None; mean, var, gamma, beta: FP32 [M] (gamma and beta together or not at
+    all).  Returns (w', b') in FP64, unrounded, w' shaped like w.
+    """
+    lib = _load()
+    w = np.asarray(w)
+    M = int(w.shape[0])
+    per = int(w.size // M)
+    stats = np.ascontiguousarray(np.concatenate([np.asarray(mean, dtype=np.float32).reshape(-1),
+                                                 np.asarray(var, dtype=np.float32).reshape(-1)]))
+    if stats.size != 2 * M or (gamma is None) != (beta is None):
+        raise ValueError("mean and var need M values each; gamma and beta come together")
+    gb = None
+    if gamma is not None:
+        gb = np.ascontiguousarray(np.concatenate([np.asarray(gamma, dtype=np.float32).reshape(-1),
+                                                  np.asarray(beta, dtype=np.float32).reshape(-1)]))
+        if gb.size != 2 * M:
+            raise ValueError("gamma and beta need M values each")
+    f32p = ctypes.POINTER(ctypes.c_float)
+    f64p = ctypes.POINTER(ctypes.c_double)
+    wk, wp = _u16(w)
+    bk, bp = _u16(b)
+    wo = np.empty(w.shape, dtype=np.float64)
+    bo = np.empty(M, dtype=np.float64)
+    rc = lib.hgo_batch_norm_fold(M, per, float(eps), float(stat_scale), wp, bp, stats.ctypes.data_as(f32p),
+                                 gb.ctypes.data_as(f32p) if gb is not None else f32p(),
+                                 wo.ctypes.data_as(f64p), bo.ctypes.data_as(f64p))
+    if rc:
+        raise ValueError(f"oracle rejected the request (rc={rc})")
+    return wo, bo
 
 
 def check_batch_norm(y, pre, mag, relu):

@@ -101,3 +101,30 @@ int hgo_batch_norm_forward(const int32_t *desc, double eps, double stat_scale, c
     }
     return 0;
 }
+
+/*
+ * Folding stored batch-norm statistics (and the scale layer) into the convolution that feeds it,
+ * once, before inference -- the pattern of Section 3.3 (conversion work is paid offline, none is
+ * left on the path): with a[m] = gamma[m] / sqrt(stat_scale * var[m] + eps),
+ *
+ *   w'[m][c][r][q] = a[m] * w[m][c][r][q]
+ *   b'[m]          = a[m] * (b[m] - stat_scale * mean[m]) + beta[m]
+ *
+ * so that conv(x, w', b') = batchnorm(conv(x, w, b)) in exact arithmetic.  w: M*per FP16 bit
+ * patterns (per = C/group * k * k), b: M FP16 bit patterns or NULL (zero); stats = M means then
+ * M variances, gamma_beta = M gammas then M betas or NULL (1 and 0), all FP32.  Outputs are FP64
+ * and unrounded: w_out M*per, b_out M.  Returns 0 or -1.
+ */
+int hgo_batch_norm_fold(int M, int per, double eps, double stat_scale, const uint16_t *w, const uint16_t *b,
+                        const float *stats, const float *gamma_beta, double *w_out, double *b_out)
+{
+    if (M < 1 || per < 1 || !(eps > 0.0) || !w || !stats || !w_out || !b_out) return -1;
+    for (int m = 0; m < M; ++m) {
+        const double g = gamma_beta ? (double)gamma_beta[m] : 1.0;
+        const double bt = gamma_beta ? (double)gamma_beta[M + m] : 0.0;
+        const double a = g / sqrt(stat_scale * (double)stats[M + m] + eps);
+        for (int i = 0; i < per; ++i) w_out[(size_t)m * per + i] = a * bn_half_to_double(w[(size_t)m * per + i]);
+        b_out[m] = a * ((b ? bn_half_to_double(b[m]) : 0.0) - stat_scale * (double)stats[m]) + bt;
+    }
+    return 0;
+}

@@ -168,6 +168,47 @@ def test_rejects_bad_requests(oracle):
         oracle.batch_norm_forward((1, 2, 1, 1, 0, 0, 0), x)
 
 
+# ---- folding stored statistics into the convolution in front (Section 3.3's pattern) -----------
+
+def test_fold_by_hand(oracle):
+    """a = gamma / sqrt(scale * var + eps): channel 0: 2 / sqrt(0.5 * 18 + 7) = 0.5; channel 1: -1 / sqrt(0.5 * 4 + 7) = -1/3."""
+    w = np.array([[[[2.0, -4.0]]], [[[3.0, 6.0]]]], dtype=np.float16)          # [M=2][1][1][2]
+    b = np.array([1.0, -2.0], dtype=np.float16)
+    wo, bo = oracle.batch_norm_fold(w, b, mean=[4.0, 2.0], var=[18.0, 4.0], eps=7.0, stat_scale=0.5,
+                                    gamma=[2.0, -1.0], beta=[0.25, 1.0])
+    assert np.array_equal(wo[0], np.array([[[1.0, -2.0]]]))                     # 0.5 * w
+    assert np.allclose(wo[1], np.array([[[-1.0, -2.0]]]), rtol=1e-15)           # -w / 3
+    assert bo[0] == 0.5 * (1.0 - 2.0) + 0.25                                    # a (b - scale * mean) + beta
+    assert abs(bo[1] - (-(-2.0 - 1.0) / 3.0 + 1.0)) < 1e-15
+    w1, b1 = oracle.batch_norm_fold(w, None, mean=[0.0, 0.0], var=[1.0, 1.0], eps=3.0)   # no bias, no scale layer
+    assert np.array_equal(w1, w.astype(np.float64) / 2.0) and np.array_equal(b1, np.zeros(2))
+
+
+def test_fold_reproduces_batch_norm_after_convolution(oracle):
+    """conv(x, w', b') = batchnorm(conv(x, w, b)): the convolution oracle and the batch-norm oracle on one side,
+    the folded parameters in a brute-force FP64 convolution on the other."""
+    N, C, H, W, M, k = 2, 3, 5, 6, 4, 3
+    x = _rand((N, C, H, W), 31)
+    w = _rand((M, C, k, k), 32, scale=0.3)
+    b = _rand((M,), 33)
+    mean = np.array([0.5, -1.0, 0.0, 2.0], dtype=np.float32)
+    var = np.array([2.0, 0.5, 1.0, 4.0], dtype=np.float32)
+    gamma = np.array([1.0, -2.0, 0.5, 1.5], dtype=np.float32)
+    beta = np.array([0.0, 1.0, -1.0, 0.25], dtype=np.float32)
+    pre, _ = oracle.conv2d_forward((N, C, H, W, M, k, 1, 1, 1, 1, 0), x, w, b)
+    sd = np.sqrt(var.astype(np.float64) + 1e-3)
+    want = gamma.astype(np.float64)[None, :, None, None] * (pre - mean.astype(np.float64)[None, :, None, None]) \
+        / sd[None, :, None, None] + beta.astype(np.float64)[None, :, None, None]
+    wo, bo = oracle.batch_norm_fold(w, b, mean, var, eps=1e-3, gamma=gamma, beta=beta)
+    xp = np.zeros((N, C, H + 2, W + 2))
+    xp[:, :, 1:-1, 1:-1] = x.astype(np.float64)
+    got = np.empty_like(want)
+    for oh in range(H):
+        for ow in range(W):
+            got[:, :, oh, ow] = np.einsum("ncrq,mcrq->nm", xp[:, :, oh:oh + k, ow:ow + k], wo) + bo[None, :]
+    assert np.allclose(got, want, rtol=1e-12, atol=1e-12)
+
+
 # ---- the paper's two devices, replayed in emulated FP16 (Section 3.1) ------------------------
 
 def _fp16_running_sum(v):
