@@ -273,6 +273,29 @@ hgc_status hgc_batch_norm_forward(const hgc_batch_norm_desc *desc, const void *x
                                   size_t workspace_bytes, void *stream);
 
 /*
+ * Stored batch-norm statistics (and the scale layer) folded into the convolution in front of
+ * them, once, before inference: the pattern of Section 3.3, where conversion work is paid
+ * offline and none is left on the path.  With a[m] = gamma[m] / sqrt(stat_scale*var[m] + eps):
+ *
+ *   w_out[m][c][r][q] = a[m] * w[m][c][r][q]
+ *   b_out[m]          = a[m] * (b[m] - stat_scale*mean[m]) + beta[m]
+ *
+ * so that the convolution with (w_out, b_out) and bias = 1 computes batch norm after the
+ * convolution with (w, b), ReLU included if the folded layer's descriptor asks for it, at the
+ * cost of one more FP16 rounding per weight.  conv: the convolution's descriptor (host; N, H, W,
+ * stride, pad and relu are not used).  w, w_out: [num_output][C/group][kernel][kernel] FP16;
+ * b (NULL iff conv->bias = 0, read as zero), b_out: [num_output] FP16; mean, var: FP32
+ * [num_output]; gamma, beta: FP32 [num_output], both or neither (1 and 0); all in device memory,
+ * caller-owned; w_out may be w and b_out may be b.  FP64 arithmetic, one rounding per value.
+ * Enqueues on `stream` and returns.  Errors, in this order: HGC_ERR_NULL, HGC_ERR_BAD_DESC (C,
+ * num_output, kernel or group < 1 or not divisible; bias not 0/1; eps or stat_scale not a
+ * positive finite number), HGC_ERR_TOO_LARGE; then HGC_ERR_LAUNCH.
+ */
+hgc_status hgc_batch_norm_fold(const hgc_conv2d_desc *conv, const void *w, const void *b, const float *mean,
+                               const float *var, float stat_scale, float eps, const float *gamma,
+                               const float *beta, void *w_out, void *b_out, void *stream);
+
+/*
  * Max-pooling layer forward: BVLC Caffe's MAX pooling, which sits between the convolutions of
  * the networks the paper runs (Section 4; the paper keeps Caffe's layers, Sections 2 and 5).
  * Square window `kernel`, stride, symmetric padding pad < kernel:

@@ -13,5 +13,5 @@ from .binding import (  # noqa: F401
     conv2d_forward_packed, igemm_variant_name, conv2d_tune, conv2d_tune_reset, tune_raw, conv2d_set_launch_shape, InnerProductDesc,
     inner_product_forward, inner_product_forward_raw, BatchNormDesc, batch_norm_forward, batch_norm_forward_raw,
     batch_norm_workspace_size, batch_norm_workspace_size_raw, MaxPoolDesc, max_pool_forward, max_pool_forward_raw,
-    max_pool_output_size, max_pool_output_size_raw,
+    max_pool_output_size, max_pool_output_size_raw, batch_norm_fold, batch_norm_fold_raw,
 )

@@ -153,6 +153,8 @@ def load():
     lib.hgc_batch_norm_workspace_size.restype = ctypes.c_int32
     lib.hgc_batch_norm_forward.argtypes = [bp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
     lib.hgc_batch_norm_forward.restype = ctypes.c_int32
+    lib.hgc_batch_norm_fold.argtypes = [dp, vp, vp, vp, vp, ctypes.c_float, ctypes.c_float, vp, vp, vp, vp, vp]
+    lib.hgc_batch_norm_fold.restype = ctypes.c_int32
     mp = ctypes.POINTER(MaxPoolDesc)
     lib.hgc_max_pool_output_size.argtypes = [mp, ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_int32)]
     lib.hgc_max_pool_output_size.restype = ctypes.c_int32
@@ -495,3 +497,31 @@ def max_pool_forward(desc, x, y=None):
     if st != 0:
         raise HgcError(st, "hgc_max_pool_forward")
     return y
+
+
+def batch_norm_fold_raw(conv: Optional[ConvDesc], w: int, b: int, mean: int, var: int, stat_scale: float, eps: float,
+                        gamma: int, beta: int, w_out: int, b_out: int, stream: int = 0) -> int:
+    dref = ctypes.byref(conv) if conv is not None else None
+    return int(load().hgc_batch_norm_fold(dref, w or None, b or None, mean or None, var or None, float(stat_scale),
+                                          float(eps), gamma or None, beta or None, w_out or None, b_out or None,
+                                          stream or None))
+
+
+def batch_norm_fold(conv, w, b, mean, var, eps: float = 1e-5, stat_scale: float = 1.0, gamma=None, beta=None):
+    """hgc_batch_norm_fold: returns (w_out, b_out), new FP16 device tensors; use them with bias = 1."""
+    import torch
+    d = ConvDesc.make(conv)
+    _check_tensor(w, "w")
+    if d.bias:
+        _check_tensor(b, "b", (d.num_output,))
+    for t, name in ((mean, "mean"), (var, "var"), (gamma, "gamma"), (beta, "beta")):
+        if t is not None and (t.dtype != torch.float32 or not t.is_cuda or not t.is_contiguous() or t.numel() != d.num_output):
+            raise ValueError(f"{name} must be a contiguous float32 device tensor of num_output elements")
+    w_out = torch.empty_like(w)
+    b_out = torch.empty(d.num_output, dtype=torch.float16, device=w.device)
+    ptr = lambda t: 0 if t is None else t.data_ptr()
+    st = batch_norm_fold_raw(d, w.data_ptr(), ptr(b) if d.bias else 0, ptr(mean), ptr(var), stat_scale, eps, ptr(gamma),
+                             ptr(beta), w_out.data_ptr(), b_out.data_ptr(), torch.cuda.current_stream(w.device).cuda_stream)
+    if st != 0:
+        raise HgcError(st, "hgc_batch_norm_fold")
+    return w_out, b_out

@@ -486,9 +486,74 @@ static hipError_t bn_launch(const BnArgs &a, bool batch_stats, hipStream_t s)
     return hipGetLastError();
 }
 
+// Offline folding of stored statistics into the convolution in front: one thread per weight (and
+// one per bias), FP64 arithmetic, one rounding to FP16 per value.
+struct FoldArgs {
+    const uint16_t *w, *b;
+    const float *mean, *var, *gamma, *beta;
+    uint16_t *w_out, *b_out;
+    uint32_t per, total;      // weights per output channel, all weights
+    int M;
+    float eps, stat_scale;
+    FastDiv fd_per;
+};
+
+__device__ __forceinline__ double bn_fold_scale(const FoldArgs &a, int m)
+{
+    const double g = a.gamma ? (double)a.gamma[m] : 1.0;
+    return g / sqrt((double)a.stat_scale * (double)a.var[m] + (double)a.eps);
+}
+
+__global__ __launch_bounds__(256) void bn_fold_kernel(const FoldArgs a)
+{
+    const uint32_t i = blockIdx.x * 256u + threadIdx.x;
+    if (i < a.total) {
+        const int m = (int)fast_div(i, a.fd_per);
+        const double wv = (double)__builtin_bit_cast(_Float16, a.w[i]);
+        a.w_out[i] = __builtin_bit_cast(uint16_t, (_Float16)(bn_fold_scale(a, m) * wv));
+    }
+    if (i < (uint32_t)a.M) {
+        const double bv = a.b ? (double)__builtin_bit_cast(_Float16, a.b[i]) : 0.0;
+        const double bt = a.beta ? (double)a.beta[i] : 0.0;
+        const double r = bn_fold_scale(a, (int)i) * (bv - (double)a.stat_scale * (double)a.mean[i]) + bt;
+        a.b_out[i] = __builtin_bit_cast(uint16_t, (_Float16)r);
+    }
+}
+
 }  // namespace hgc
 
 using namespace hgc;
+
+extern "C" hgc_status hgc_batch_norm_fold(const hgc_conv2d_desc *conv, const void *w, const void *b, const float *mean,
+                                          const float *var, float stat_scale, float eps, const float *gamma,
+                                          const float *beta, void *w_out, void *b_out, void *stream)
+{
+    if (!conv || !w || !mean || !var || !w_out || !b_out) return HGC_ERR_NULL;
+    if (conv->bias == 1 && !b) return HGC_ERR_NULL;
+    if ((gamma == nullptr) != (beta == nullptr)) return HGC_ERR_NULL;
+    if (conv->C < 1 || conv->num_output < 1 || conv->kernel < 1 || conv->group < 1 || conv->C % conv->group != 0 ||
+        conv->num_output % conv->group != 0 || (conv->bias != 0 && conv->bias != 1))
+        return HGC_ERR_BAD_DESC;
+    if (!(eps > 0.0f && eps < 3.0e38f) || !(stat_scale > 0.0f && stat_scale < 3.0e38f)) return HGC_ERR_BAD_DESC;
+    const long long per = (long long)(conv->C / conv->group) * conv->kernel * conv->kernel;
+    if (per * conv->num_output > 0x7FFFFFFFLL) return HGC_ERR_TOO_LARGE;
+    FoldArgs a;
+    a.w = static_cast<const uint16_t *>(w);
+    a.b = conv->bias ? static_cast<const uint16_t *>(b) : nullptr;
+    a.mean = mean; a.var = var; a.gamma = gamma; a.beta = beta;
+    a.w_out = static_cast<uint16_t *>(w_out);
+    a.b_out = static_cast<uint16_t *>(b_out);
+    a.per = (uint32_t)per;
+    a.total = (uint32_t)(per * conv->num_output);
+    a.M = conv->num_output;
+    a.eps = eps; a.stat_scale = stat_scale;
+    a.fd_per = make_fastdiv(a.per);
+    const uint32_t threads = a.total > (uint32_t)a.M ? a.total : (uint32_t)a.M;
+    bn_fold_kernel<<<dim3((threads + 255) / 256), dim3(256), 0, static_cast<hipStream_t>(stream)>>>(a);
+    const hipError_t e = hipGetLastError();
+    set_last_hip_error(e);
+    return e == hipSuccess ? HGC_OK : HGC_ERR_LAUNCH;
+}
 
 extern "C" hgc_status hgc_batch_norm_workspace_size(const hgc_batch_norm_desc *desc, size_t *bytes)
 {

@@ -201,6 +201,25 @@ def test_batch_norm_validates_on_the_host(lib):
     assert hgc.batch_norm_forward_raw(good, FAKE, 0, 0, 0, 0, FAKE, FAKE, need - 1) == -4
 
 
+def test_batch_norm_fold_validates_on_the_host(lib):
+    d = ConvDesc(1, 16, 8, 8, 32, 3, 1, 1, 1, 1, 1)
+    f = lambda conv, *p, ss=1.0, eps=1e-5: hgc.batch_norm_fold_raw(conv, p[0], p[1], p[2], p[3], ss, eps, p[4], p[5], p[6], p[7])
+    ok = (FAKE,) * 8
+    assert f(None, *ok) == -1
+    for missing in (0, 1, 2, 3, 6, 7):                        # w, b (bias = 1), mean, var, w_out, b_out
+        p = list(ok); p[missing] = 0
+        assert f(d, *p) == -1
+    p = list(ok); p[4] = 0
+    assert f(d, *p) == -1                                     # gamma without beta
+    nobias = ConvDesc(1, 16, 8, 8, 32, 3, 1, 1, 1, 0, 1)
+    p = list(ok); p[1] = 0
+    assert f(ConvDesc(1, 16, 8, 8, 32, 3, 1, 1, 3, 0, 1), *p) == -2      # 16 channels in 3 groups
+    assert f(ConvDesc(1, 0, 8, 8, 32, 3, 1, 1, 1, 0, 1), *p) == -2
+    assert f(nobias, *p, eps=0.0) == -2
+    assert f(nobias, *p, ss=-1.0) == -2
+    assert f(ConvDesc(1, 1 << 14, 8, 8, 1 << 14, 3, 1, 1, 1, 0, 1), *p) == -3
+
+
 def test_max_pool_validates_on_the_host(lib):
     """hgc_max_pool_forward / hgc_max_pool_output_size: NULL, BAD_DESC, TOO_LARGE before any GPU work."""
     mp = hgc.MaxPoolDesc

@@ -220,3 +220,45 @@ def test_binding_wrapper(oracle):
     check(oracle, (N, C, H, W, 0, 0, 0), x, y.cpu().numpy(), "wrapper", gmean=mean.cpu().numpy(), gvar=var.cpu().numpy())
     with pytest.raises(ValueError):
         hgc.batch_norm_forward((N, C, H, W, 1, 0, 0), xd)
+
+
+def test_fold_into_the_convolution(oracle):
+    """hgc_batch_norm_fold: the folded parameters are the oracle's, rounded once; and the folded convolution on
+    the GPU computes batch norm after the convolution as the two oracles define it.  Bound of the second
+    check: the unfolded pair would be allowed |a| (4e-3 mag + 1e-3) from the convolution plus the batch norm's
+    own rounding; folding rounds every weight once more (2^-11 of |a| mag, inside the first term) and the
+    bias once (2^-11 |b'|)."""
+    import torch
+    from workloads import ConvLayer, make_tensors
+    for L in [ConvLayer("fold.a", 2, 16, 14, 14, 32, 3, 1, 1), ConvLayer("fold.b", 1, 8, 9, 9, 12, 1, 1, 0, 1, 0, 0),
+              ConvLayer("fold.c", 2, 12, 10, 10, 24, 3, 2, 1, 4)]:
+        x, w, b = make_tensors(L, seed=77)
+        M = L.M
+        mean = (2.0 * uniform01(9, 1, M) - 1.0).astype(np.float32) * 4
+        var = (0.2 + 2.0 * uniform01(9, 2, M)).astype(np.float32) * 4
+        gamma, beta = affine(M, seed=9)
+        eps, scale = 1e-3, 0.25
+        for with_scale in (True, False):
+            g, bt = (gamma, beta) if with_scale else (None, None)
+            say(f"[bn-fold] {L.name} scale layer {with_scale}")
+            dev = lambda a: None if a is None else torch.from_numpy(np.ascontiguousarray(a)).cuda()
+            wo, bo = hgc.batch_norm_fold(L, dev(w), dev(b) if L.bias else None, dev(mean), dev(var), eps=eps,
+                                         stat_scale=scale, gamma=dev(g), beta=dev(bt))
+            torch.cuda.synchronize()
+            w64, b64 = oracle.batch_norm_fold(w, b if L.bias else None, mean, var, eps=eps, stat_scale=scale, gamma=g, beta=bt)
+            assert np.array_equal(wo.cpu().numpy(), w64.astype(np.float16))
+            assert np.array_equal(bo.cpu().numpy(), b64.astype(np.float16))
+            folded = ConvLayer(L.name, L.N, L.C, L.H, L.W, L.M, L.k, L.s, L.p, L.G, 1, 1)
+            ws = torch.empty(max(1, hgc.conv2d_workspace_size(folded)), dtype=torch.uint8, device="cuda")
+            y = hgc.conv2d_forward_ws(folded, dev(x), wo, bo, None, ws)
+            torch.cuda.synchronize()
+            pre, mag = oracle.conv2d_forward(L.desc(), x, w, b if L.bias else None)
+            a = (g.astype(np.float64) if with_scale else 1.0) / np.sqrt(scale * var.astype(np.float64) + eps)
+            ref = a[None, :, None, None] * (pre - scale * mean.astype(np.float64)[None, :, None, None]) \
+                + (bt.astype(np.float64)[None, :, None, None] if with_scale else 0.0)
+            ref = np.maximum(ref, 0.0)
+            bound = np.abs(a)[None, :, None, None] * (4e-3 * mag + 1e-3) + 2.0 ** -11 * np.abs(b64)[None, :, None, None] \
+                + 1e-3 * np.abs(ref) + 1e-3
+            err = np.abs(y.cpu().numpy().astype(np.float64) - ref)
+            worst = np.unravel_index(np.argmax(err / bound), err.shape)
+            assert np.all(err <= bound), f"{L.name}: |err| {err[worst]} > {bound[worst]} at {worst}"
