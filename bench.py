@@ -336,15 +336,20 @@ def main() -> int:
         sample = [i for i, L in enumerate(layers)] if args.batch == 1 else [len(layers) - 1]
         t = time.perf_counter()
         fl = 0
-        for i in sample:
-            x, w, b = host[i]
-            oracle.conv2d_forward(layers[i].desc(), x, w, b)
-            fl += layers[i].flops
-        dt = time.perf_counter() - t
+        passes = 0
+        while True:                                   # whole passes until about ten seconds of CPU work are in
+            for i in sample:
+                x, w, b = host[i]
+                oracle.conv2d_forward(layers[i].desc(), x, w, b)
+                fl += layers[i].flops
+            passes += 1
+            dt = time.perf_counter() - t
+            if dt >= 10.0 or passes >= 50:
+                break
         cpu = {"value": fl / dt / 1e12, "unit": "TFLOP/s", "cores": oracle.num_threads(), "kind": "oracle",
-               "sample": "one pass over %d of the %d layers at N=%d (%.2f GFLOP, %.1f s)" % (
-                   len(sample), len(layers), args.batch, fl / 1e9, dt),
-               "ms_per_image": dt * 1e3 / args.batch if len(sample) == len(layers) else None}
+               "sample": "%d pass%s over %d of the %d layers at N=%d (%.2f GFLOP, %.1f s)" % (
+                   passes, "" if passes == 1 else "es", len(sample), len(layers), args.batch, fl / 1e9, dt),
+               "ms_per_image": dt * 1e3 / passes / args.batch if len(sample) == len(layers) else None}
 
     out = {
         "metric": "FP16 conv-forward TFLOP/s, VGG-16-shaped 13-layer stack",
