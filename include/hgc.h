@@ -73,6 +73,8 @@ typedef int32_t hgc_status;
 #define HGC_PATH_DEPTHWISE  4    /* group == C == num_output streaming kernel           */
 #define HGC_PATH_FIRST_LAYER 5   /* C <= 4, one group, kernel 3/5/7, packed weights: MFMA
                                     with horizontal tap pairs folded into the reduction  */
+#define HGC_PATH_POINTWISE  6    /* kernel 1, stride 1, pad 0, one group, C % 32 == 0, H*W % 4 == 0,
+                                    16-byte aligned tensors: GEMM over the pixels of all images */
 
 /* What a call will do for a descriptor; filled by hgc_conv2d_plan. */
 typedef struct hgc_plan {

@@ -7,7 +7,7 @@ there is no CPU fallback: loading fails loudly when libhgc.so is missing.
 """
 from .binding import (  # noqa: F401
     ConvDesc, Plan, HgcError, PATH_AUTO, PATH_DIRECT, PATH_IGEMM, PATH_IGEMM_SPLITK,
-    PATH_DEPTHWISE, PATH_FIRST_LAYER, PATH_NAMES, load, library_path, conv2d_forward, conv2d_forward_ws,
+    PATH_DEPTHWISE, PATH_FIRST_LAYER, PATH_POINTWISE, PATH_NAMES, load, library_path, conv2d_forward, conv2d_forward_ws,
     conv2d_workspace_size, conv2d_plan, set_forced_path, set_forced_tiling, status_string, version,
     forward_raw, forward_ws_raw, forward_packed_raw, conv2d_packed_weights_size, conv2d_pack_weights,
     conv2d_forward_packed, igemm_variant_name, conv2d_tune, conv2d_tune_reset, tune_raw, conv2d_set_launch_shape, InnerProductDesc,

@@ -16,7 +16,8 @@ _lib = None
 
 PATH_AUTO, PATH_DIRECT, PATH_IGEMM, PATH_IGEMM_SPLITK, PATH_DEPTHWISE = 0, 1, 2, 3, 4
 PATH_FIRST_LAYER = 5
-PATH_NAMES = {1: "direct", 2: "igemm", 3: "igemm_splitk", 4: "depthwise", 5: "first_layer"}
+PATH_POINTWISE = 6
+PATH_NAMES = {1: "direct", 2: "igemm", 3: "igemm_splitk", 4: "depthwise", 5: "first_layer", 6: "pointwise"}
 
 
 class HgcError(RuntimeError):
@@ -119,6 +120,9 @@ def load():
         raise ImportError(
             f"{_LIB_PATH} is missing: build it with `python -m paper_1901_00858_amd.build` "
             "(or __graft_entry__.build()); there is no fallback implementation")
+    # PyTorch brings its own copy of the HIP runtime; whichever copy is loaded first serves the whole
+    # process, and device memory and streams come from PyTorch's, so it has to be that one
+    import torch  # noqa: F401
     lib = ctypes.CDLL(_LIB_PATH)
     vp, dp = ctypes.c_void_p, ctypes.POINTER(ConvDesc)
     lib.hgc_conv2d_forward.argtypes = [dp, vp, vp, vp, vp, vp]

@@ -110,12 +110,15 @@ static Geometry kernel_geometry(const Geometry &g)
     return f;
 }
 
+constexpr long long kPointwiseMinBlocks = 192;
+
 struct Plan {
     hgc_plan pub;
     ConvArgs args;
     const IgemmVariant *variant;
     double cycles;       // the cost model's estimate (implicit-GEMM paths)
-    int first_a, first_xv;   // first-layer kernel: 32-row blocks per workgroup, input pixels per load
+    int first_a, first_xv;   // first-layer kernel: 32-row blocks per workgroup, input pixels per load;
+                             // pointwise kernel: 64-row and 64-pixel blocks per workgroup
 };
 
 static void base_args(const Geometry &g, ConvArgs *a)
@@ -326,7 +329,7 @@ static bool plan_igemm(const Geometry &g, bool with_ws, int x_align, bool w_al16
 }
 
 static void make_plan(const Geometry &g0, bool with_ws, int x_align, bool w_al16, bool packed, Plan *pl,
-                      const Forced *tuned = nullptr)
+                      const Forced *tuned = nullptr, bool allow_pointwise = true)
 {
     const Geometry g = kernel_geometry(g0);
     std::memset(pl, 0, sizeof(*pl));
@@ -346,12 +349,32 @@ static void make_plan(const Geometry &g0, bool with_ws, int x_align, bool w_al16
     const bool depthwise_ok = (g.G == g.C && g.M == g.C && (g.k == 3 || g.k == 5));
     const bool first_ok = packed && g.G == 1 && g.C <= 4 && (g.k == 3 || g.k == 5 || g.k == 7) && g.M >= 16;
 
+    // 1x1 layers as a GEMM over all images' pixels: taken once the tiles fill most of the chip (below
+    // that the implicit-GEMM kernels' reduction split keeps more compute units busy)
+    const bool pointwise_ok = allow_pointwise && pointwise_eligible(pl->args, x_align, 16, w_al16);
+    int pw_a = 2, pw_b = 2;
+    if (pointwise_ok) pointwise_tile(pl->args, &pw_a, &pw_b);
+    const long long pw_blocks = pointwise_ok
+        ? (long long)ceil_div(g.M, 64 * pw_a) * ceil_div((long long)g.N * g.H * g.W, 64 * pw_b) : 0;
+
     int path = forced;
     if (path == HGC_PATH_AUTO) {
         if (depthwise_ok) path = HGC_PATH_DEPTHWISE;
         else if (first_ok) path = HGC_PATH_FIRST_LAYER;
+        else if (pointwise_ok && pw_blocks >= kPointwiseMinBlocks && !use_tuned) path = HGC_PATH_POINTWISE;
         else if (g.Mg >= 16) path = HGC_PATH_IGEMM;
         else path = HGC_PATH_DIRECT;
+    }
+    if (path == HGC_PATH_POINTWISE) {
+        if (pointwise_ok) {
+            pl->pub.path = HGC_PATH_POINTWISE;
+            pl->pub.tile_m = 64 * pw_a; pl->pub.tile_h = 1; pl->pub.tile_w = 64 * pw_b;
+            pl->pub.grid = (int)pw_blocks; pl->pub.block = 256; pl->pub.variant = -1;
+            pl->pub.lds_bytes = 2LL * (32 * (128 * pw_b + 64) + 64 * pw_a * 80);   // two stages of {input rows, weight rows}
+            pl->first_a = pw_a; pl->first_xv = pw_b;
+            return;
+        }
+        path = g.Mg >= 16 ? HGC_PATH_IGEMM : HGC_PATH_DIRECT;
     }
     if (path == HGC_PATH_DEPTHWISE && depthwise_ok) {
         pl->pub.path = HGC_PATH_DEPTHWISE;
@@ -470,6 +493,8 @@ static hgc_status prepare(const hgc_conv2d_desc *desc, const void *x, const void
             tuned_lookup(key, &tuned))
             make_plan(g, with_ws, x_align, w_al16, packed, &pl);
     }
+    if (pl.pub.path == HGC_PATH_POINTWISE && ((uintptr_t)y & 15))   // the plan assumed a 16-byte aligned y
+        make_plan(g, with_ws, x_align, w_al16, packed, &pl, nullptr, false);
     if (pl.pub.workspace_bytes > 0) {
         // the size reported to the caller assumed aligned tensors; an unaligned call
         // may need the same or less, never more (same tiles, same split rule)
@@ -514,6 +539,9 @@ static hipError_t enqueue(const Plan &pl, hipStream_t s)
         break;
     case HGC_PATH_FIRST_LAYER:
         e = launch_smallc(a, pl.first_a, pl.first_xv, (size_t)pl.pub.lds_bytes, s);
+        break;
+    case HGC_PATH_POINTWISE:
+        e = launch_pointwise(a, pl.first_a, pl.first_xv, s);
         break;
     case HGC_PATH_IGEMM:
     case HGC_PATH_IGEMM_SPLITK:
@@ -688,7 +716,7 @@ hgc_status hgc_conv2d_plan(const hgc_conv2d_desc *desc, int32_t with_workspace, 
 
 int32_t hgc_set_forced_path(int32_t path, int32_t tile_variant)
 {
-    if (path < HGC_PATH_AUTO || path > HGC_PATH_FIRST_LAYER) path = HGC_PATH_AUTO;
+    if (path < HGC_PATH_AUTO || path > HGC_PATH_POINTWISE) path = HGC_PATH_AUTO;
     g_forced_variant.store(tile_variant, std::memory_order_relaxed);
     const int32_t before = g_forced_path.exchange(path, std::memory_order_relaxed);
     g_plan_epoch.fetch_add(1, std::memory_order_release);

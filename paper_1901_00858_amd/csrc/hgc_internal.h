@@ -137,6 +137,12 @@ PackedLayout packed_layout(const Geometry &g);
 hipError_t launch_pack_weights(const Geometry &g, const PackedLayout &pl, const uint16_t *w, uint8_t *packed,
                                hipStream_t stream);
 
+// 1x1 / stride 1 / unpadded / one-group layers as a GEMM over all images' pixels (pointwise.hip):
+// whether the kernel takes the layer (alignments in bytes), its tile (64 a rows x 64 b pixels), the launch
+bool pointwise_eligible(const ConvArgs &c, int x_align, int y_align, bool w_al16);
+void pointwise_tile(const ConvArgs &c, int *a, int *b);
+hipError_t launch_pointwise(const ConvArgs &c, int a, int b, hipStream_t stream);
+
 // records the runtime error behind the calling thread's latest HGC_ERR_LAUNCH (hgc_last_launch_error)
 void set_last_hip_error(hipError_t e);
 
