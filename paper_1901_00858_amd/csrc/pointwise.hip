@@ -254,7 +254,7 @@ template <int A, int B>
 static hipError_t pw_launch(const PwArgs &a, int v, unsigned blocks, hipStream_t s)
 {
     // stages in flight: what the registers allow, and a divisor of the number of stages
-    constexpr int DMAX = B >= 4 ? 2 : 4;
+    constexpr int DMAX = (B >= 4 || A >= 4) ? 2 : 4;
     const int stages = a.C / kPwKC;
     const int d = (stages % 4 == 0 && DMAX >= 4) ? 4 : (stages % 2 == 0 ? 2 : 1);
     if (v == 8) {
@@ -284,6 +284,8 @@ void pointwise_tile(const ConvArgs &c, int *a, int *b)
     *a = c.M <= 64 ? 1 : 2;                         // 64 rows a workgroup when there are no more
     const long long big = ((c.M + 64 * *a - 1) / (64 * *a)) * ((Q + 255) / 256);
     *b = big >= 512 ? 4 : 2;
+    // 256 rows x 128 pixels re-read x half as often from L2; measured to pay from about 1.5 workgroups per compute unit on
+    if (*b == 2 && c.M >= 256 && ((c.M + 255) / 256) * ((Q + 127) / 128) >= 384) *a = 4;
 }
 
 hipError_t launch_pointwise(const ConvArgs &c, int a, int b, hipStream_t s)
@@ -303,6 +305,7 @@ hipError_t launch_pointwise(const ConvArgs &c, int a, int b, hipStream_t s)
     const unsigned blocks = (p.tiles + 7u) / 8u * 8u;
     const int v = p.P % 8 == 0 ? 8 : 4;
     if (a == 1) return b == 4 ? pw_launch<1, 4>(p, v, blocks, s) : pw_launch<1, 2>(p, v, blocks, s);
+    if (a == 4) return pw_launch<4, 2>(p, v, blocks, s);
     return b == 4 ? pw_launch<2, 4>(p, v, blocks, s) : pw_launch<2, 2>(p, v, blocks, s);
 }
 

@@ -34,6 +34,7 @@ SHAPES = [
     (9, 64, 14, 14, 256),       # 1764 pixels: 14 pixel tiles of 128, the last ragged, two row tiles
     (84, 64, 28, 28, 128),      # 65856 pixels: enough tiles for the wide (256-pixel) tile
     (42, 32, 56, 56, 64),       # the wide tile with 64 rows a workgroup (M <= 64), a single stage
+    (32, 64, 28, 28, 300),      # 256 rows a workgroup, the second row tile ragged
 ]
 
 
