@@ -110,54 +110,99 @@ __global__ __launch_bounds__(256) void depthwise3_vec_kernel(const ConvArgs p)
 {
     constexpr int VI = VO * STRIDE;
     constexpr int RI = (RO - 1) * STRIDE + 3;      // input rows per thread
-    typedef uint16_t hv __attribute__((ext_vector_type(VI)));
+    constexpr uint32_t kNone = 0xFFFFFFFFu;        // an offset beyond any buffer: such a load returns zero
     typedef uint16_t ho __attribute__((ext_vector_type(VO)));
-    const int GW = p.Wo / VO;                      // thread groups per output row
-    const int GH = (p.Ho + RO - 1) / RO;           // row groups per plane
-    const long long items = (long long)p.N * p.C * GH * GW;
-    const int lane = threadIdx.x & 63;
-    for (long long t = (long long)blockIdx.x * 256 + threadIdx.x; t - lane < items;
-         t += (long long)gridDim.x * 256) {
+    typedef uint32_t dw_u32x2 __attribute__((ext_vector_type(2)));
+    typedef uint32_t dw_u32x4 __attribute__((ext_vector_type(4)));
+    const uint32_t GW = p.fd_tiles_w.d;            // thread groups per output row (Wo / VO)
+    const uint32_t GH = p.fd_tiles_h.d;            // row groups per plane
+    const uint32_t items = (uint32_t)p.N * (uint32_t)p.C * GH * GW;
+    const uint32_t lane = threadIdx.x & 63;
+    const __amdgpu_buffer_rsrc_t rx =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t *>(p.x), 0, p.x_bytes, 0x00020000);
+    for (uint32_t t = blockIdx.x * 256u + threadIdx.x; t - lane < items; t += gridDim.x * 256u) {
         const bool live = t < items;               // whole waves stay in the loop: shuffles need every lane
-        const long long tt = live ? t : items - 1;
-        const int owg = (int)(tt % GW);
-        const long long u = tt / GW;
-        const int oh0 = (int)(u % GH) * RO;
-        const long long nc = u / GH;
-        const int c = (int)(nc % p.C);
+        const uint32_t tt = live ? t : items - 1;
+        const uint32_t u = fast_div(tt, p.fd_tiles_w);
+        const int owg = (int)(tt - u * GW);
+        const uint32_t nc = fast_div(u, p.fd_tiles_h);
+        const int oh0 = (int)(u - nc * GH) * RO;
+        const int c = (int)(nc - fast_div(nc, p.fd_G) * (uint32_t)p.C);
         float wr[9];
 #pragma unroll
         for (int k = 0; k < 9; ++k) wr[k] = h2f(p.w[(size_t)c * 9 + k]);
         const float bv = p.bias ? h2f(p.b[c]) : 0.0f;
+        const int iw0 = owg * VI;                  // first input column of the vector; the window starts at iw0 - 1
+        const uint32_t plane = 2u * nc * (uint32_t)(p.H * p.W);      // byte offset of the (n, c) plane
+        // Every load of the item is issued before the first is used: the rows as range-checked buffer
+        // loads (a row outside the image, or an item past the end: an out-of-range offset, which reads
+        // zero), and the two halo pixels that the neighbouring lanes cannot supply (first and last lane
+        // of the wave) the same way.  A branch around each load would make each a round trip of its own.
+        // Two-pixel vectors at stride 1 (rows of 6, 10, 14 ... pixels): the window of a row is 4 pixels,
+        // 8 bytes, and one load at a 2-byte aligned address brings all of it, halo included -- no
+        // exchange between lanes, no separate halo loads.  The first group of a row loads from its own
+        // first pixel and shifts one pixel up (the left halo is padding), the last loads one pixel
+        // earlier and shifts down (the right halo is padding), so every load stays inside its row.
+        constexpr bool kWide = (VI == 2 && STRIDE == 1);
+        uint32_t raw[RI][kWide ? 2 : (VI >= 2 ? VI / 2 : 1)];
+        uint32_t edge_l[RI], edge_r[RI];
+        const bool first = owg == 0, last = owg == (int)GW - 1;
+#pragma unroll
+        for (int rr = 0; rr < RI; ++rr) {
+            const int ih = oh0 * STRIDE - 1 + rr;
+            const bool row_ok = live && ih >= 0 && ih < p.H;
+            const uint32_t at = plane + 2u * (uint32_t)(ih * p.W + iw0);
+            const uint32_t off = row_ok ? at : kNone;
+            if constexpr (kWide) {
+                const dw_u32x2 v = __builtin_amdgcn_raw_buffer_load_b64(rx, row_ok ? at - (first ? 0u : last ? 4u : 2u) : kNone, 0, 0);
+                raw[rr][0] = v.x; raw[rr][1] = v.y;
+                edge_l[rr] = edge_r[rr] = 0u;
+            } else {
+            if constexpr (VI == 8) {
+                const dw_u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rx, off, 0, 0);
+                raw[rr][0] = v.x; raw[rr][1] = v.y; raw[rr][2] = v.z; raw[rr][3] = v.w;
+            } else if constexpr (VI == 4) {
+                const dw_u32x2 v = __builtin_amdgcn_raw_buffer_load_b64(rx, off, 0, 0);
+                raw[rr][0] = v.x; raw[rr][1] = v.y;
+            } else if constexpr (VI == 2) {
+                raw[rr][0] = __builtin_amdgcn_raw_buffer_load_b32(rx, off, 0, 0);
+            } else {
+                raw[rr][0] = (uint16_t)__builtin_amdgcn_raw_buffer_load_b16(rx, off, 0, 0);
+            }
+            edge_l[rr] = (uint16_t)__builtin_amdgcn_raw_buffer_load_b16(rx, (row_ok && lane == 0 && owg != 0) ? at - 2u : kNone, 0, 0);
+            edge_r[rr] = STRIDE == 1
+                ? (uint16_t)__builtin_amdgcn_raw_buffer_load_b16(rx, (row_ok && lane == 63 && owg != (int)GW - 1) ? at + 2u * VI : kNone, 0, 0)
+                : 0u;
+            }
+        }
         float acc[RO][VO];
 #pragma unroll
         for (int o = 0; o < RO; ++o)
 #pragma unroll
             for (int j = 0; j < VO; ++j) acc[o][j] = bv;
-        const uint16_t *xp = p.x + (size_t)nc * p.H * p.W;
-        const int iw0 = owg * VI;                  // first input column of the vector; the window starts at iw0 - 1
 #pragma unroll
         for (int rr = 0; rr < RI; ++rr) {
-            const int ih = oh0 * STRIDE - 1 + rr;
-            const bool row_ok = live && ih >= 0 && ih < p.H;
             float in[VI + 2];                      // columns iw0-1 .. iw0+VI
-            hv v;
+            if constexpr (kWide) {
+                uint64_t v = ((uint64_t)raw[rr][1] << 32) | raw[rr][0];
+                v = first ? (v << 16) : last ? (v >> 16) : v;
 #pragma unroll
-            for (int j = 0; j < VI; ++j) v[j] = 0;
-            if (row_ok) v = *reinterpret_cast<const hv *>(xp + (size_t)ih * p.W + iw0);
+                for (int j = 0; j < 4; ++j) in[j] = h2f((uint16_t)(v >> (16 * j)));
+            } else {
 #pragma unroll
-            for (int j = 0; j < VI; ++j) in[j + 1] = h2f(v[j]);
+            for (int j = 0; j < VI; ++j) in[j + 1] = h2f((uint16_t)(raw[rr][j >> 1] >> (16 * (j & 1))));
             // halo columns: the neighbour lane holds the adjacent vector of the same row
             float left = __shfl_up(in[VI], 1);
             float right = __shfl_down(in[1], 1);
             if (owg == 0) left = 0.0f;             // padding column
-            else if (lane == 0) left = row_ok ? h2f(xp[(size_t)ih * p.W + iw0 - 1]) : 0.0f;
+            else if (lane == 0) left = h2f((uint16_t)edge_l[rr]);
             if (STRIDE == 1) {
-                if (owg == GW - 1) right = 0.0f;
-                else if (lane == 63) right = row_ok ? h2f(xp[(size_t)ih * p.W + iw0 + VI]) : 0.0f;
+                if (owg == (int)GW - 1) right = 0.0f;
+                else if (lane == 63) right = h2f((uint16_t)edge_r[rr]);
             }
             in[0] = left;
             in[VI + 1] = right;
+            }
             // input row rr is tap row kr of output row o when rr = o*STRIDE + kr
 #pragma unroll
             for (int kr = 0; kr < 3; ++kr) {
@@ -186,11 +231,15 @@ __global__ __launch_bounds__(256) void depthwise3_vec_kernel(const ConvArgs p)
 template <int STRIDE, int VO>
 static hipError_t launch_dw3(const ConvArgs &a, hipStream_t stream)
 {
-    constexpr int RO = (VO >= 8) ? 2 : 4;          // output rows per thread
+    constexpr int RO = (VO >= 8) ? 2 : (VO >= 4 ? 4 : 8);   // output rows per thread: narrow vectors (small maps) take more rows
     const long long items = (long long)a.N * a.C * ((a.Ho + RO - 1) / RO) * (a.Wo / VO);
     long long blocks = (items + 255) / 256;
     if (blocks > 1048576) blocks = 1048576;
-    hipLaunchKernelGGL((depthwise3_vec_kernel<STRIDE, VO, RO>), dim3((unsigned)blocks), dim3(256), 0, stream, a);
+    ConvArgs b = a;                                // item index -> (plane, row group, column group), channel of a plane
+    b.fd_tiles_w = make_fastdiv((uint32_t)(a.Wo / VO));
+    b.fd_tiles_h = make_fastdiv((uint32_t)((a.Ho + RO - 1) / RO));
+    b.fd_G = make_fastdiv((uint32_t)a.C);
+    hipLaunchKernelGGL((depthwise3_vec_kernel<STRIDE, VO, RO>), dim3((unsigned)blocks), dim3(256), 0, stream, b);
     return hipGetLastError();
 }
 
@@ -206,7 +255,7 @@ hipError_t launch_depthwise(const ConvArgs &a, hipStream_t stream)
             if (a.stride == 1) {
                 if (vi == 8) return launch_dw3<1, 8>(a, stream);
                 if (vi == 4) return launch_dw3<1, 4>(a, stream);
-                if (vi == 2) return launch_dw3<1, 2>(a, stream);
+                if (vi == 2 && a.W >= 4) return launch_dw3<1, 2>(a, stream);   // its window loads span 4 pixels of a row
                 return launch_dw3<1, 1>(a, stream);
             }
             if (vi == 8) return launch_dw3<2, 4>(a, stream);

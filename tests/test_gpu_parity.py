@@ -53,6 +53,10 @@ SHAPES = [
     (1, 8, 9, 56, 8, 3, 1, 1, 8),        # depthwise, 8-pixel vectors, halo fetched across waves
     (1, 8, 12, 28, 8, 3, 1, 1, 8),       # depthwise, 4-pixel vectors
     (1, 8, 14, 14, 8, 3, 1, 1, 8),       # depthwise, 2-pixel vectors
+    (2, 8, 9, 6, 8, 3, 1, 1, 8),         # depthwise, 2-pixel vectors, three groups a row, odd height
+    (3, 16, 5, 10, 16, 3, 1, 1, 16),     # depthwise, 2-pixel vectors, rows shorter than a wave
+    (1, 8, 7, 2, 8, 3, 1, 1, 8),         # depthwise, rows of two pixels
+    (2, 8, 30, 4, 8, 3, 1, 1, 8),        # depthwise, rows of four pixels: a first and a last group only
     (1, 8, 10, 112, 8, 3, 2, 1, 8),      # depthwise stride 2, 8-pixel input vectors
     (2, 8, 28, 28, 8, 3, 2, 1, 8),       # depthwise stride 2, 4-pixel input vectors
     (1, 8, 9, 9, 16, 3, 1, 1, 8),        # channel multiplier 2 (Mg = 2) -> direct
