@@ -341,12 +341,6 @@ __global__ __launch_bounds__(256) void bn_stored_stats_kernel(const BnArgs p)
     p.coef[c] = bn_coefficients(mu, var, gm, bt, p.eps);
 }
 
-template <int V> struct BnVec;
-template <> struct BnVec<8> { typedef bn_u32x4 type; };
-template <> struct BnVec<4> { typedef bn_u32x2 type; };
-template <> struct BnVec<2> { typedef uint32_t type; };
-template <> struct BnVec<1> { typedef uint16_t type; };
-
 __device__ __forceinline__ uint32_t bn_apply2(uint32_t u, const float4 k, bool relu)
 {
     float lo = fmaf((bn_lo(u) - k.x) - k.y, k.z, k.w), hi = fmaf((bn_hi(u) - k.x) - k.y, k.z, k.w);
@@ -359,43 +353,47 @@ __device__ __forceinline__ uint32_t bn_apply2(uint32_t u, const float4 k, bool r
 
 // y = act((x - mean[c]) a[c] + beta[c]) over the tensor taken as one flat array of V-value vectors (a plane's
 // length is a multiple of V, so a vector lies in one plane).  Each thread takes U vectors, 256
-// vectors apart, and issues its loads before the arithmetic.  y may be x itself.
+// vectors apart.  Loads and stores are range-checked buffer accesses (a vector past the end reads
+// zero and its store is dropped), so the kernel has no branch and all of a thread's loads are in
+// flight together; with an `if (inside)` around each the compiler waits for one before issuing the
+// next.  y may be x itself.
 template <int V>
 __global__ __launch_bounds__(256) void bn_apply_kernel(const BnArgs p)
 {
     constexpr int U = 4;
-    typedef typename BnVec<V>::type vec_t;
-    const vec_t *xin = reinterpret_cast<const vec_t *>(p.x);
-    vec_t *yout = reinterpret_cast<vec_t *>(p.y);
+    constexpr int NW = V >= 2 ? V / 2 : 1;
+    const __amdgpu_buffer_rsrc_t rx =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t *>(p.x), 0, p.x_bytes, 0x00020000);
+    const __amdgpu_buffer_rsrc_t ry = __builtin_amdgcn_make_buffer_rsrc(p.y, 0, p.x_bytes, 0x00020000);
     const uint32_t v0 = blockIdx.x * (256u * U) + threadIdx.x;
-    vec_t d[U];
+    uint32_t d[U][NW];
     float4 k[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
         const uint32_t vi = v0 + (uint32_t)u * 256u;
-        if (vi < p.nvec) {
-            d[u] = xin[vi];
-            const uint32_t plane = fast_div(vi * V, p.fd_HW);
-            k[u] = p.coef[plane - fast_div(plane, p.fd_C) * (uint32_t)p.C];
-        }
+        // past the end: the byte offset is beyond the buffer (nvec * V * 2 = its size; no wrap: vi < 2^29 + 2^20)
+        bn_load<V>(d[u], rx, vi < p.nvec ? vi * (2u * V) : kBnNoLoad);
+        const uint32_t plane = fast_div(min(vi, p.nvec - 1u) * V, p.fd_HW);
+        k[u] = p.coef[plane - fast_div(plane, p.fd_C) * (uint32_t)p.C];
     }
 #pragma unroll
     for (int u = 0; u < U; ++u) {
         const uint32_t vi = v0 + (uint32_t)u * 256u;
-        if (vi < p.nvec) {
-            const bool relu = p.relu != 0;
-            vec_t r;
-            if constexpr (V == 8) {
-                r.x = bn_apply2(d[u].x, k[u], relu); r.y = bn_apply2(d[u].y, k[u], relu);
-                r.z = bn_apply2(d[u].z, k[u], relu); r.w = bn_apply2(d[u].w, k[u], relu);
-            } else if constexpr (V == 4) {
-                r.x = bn_apply2(d[u].x, k[u], relu); r.y = bn_apply2(d[u].y, k[u], relu);
-            } else if constexpr (V == 2) {
-                r = bn_apply2(d[u], k[u], relu);
-            } else {
-                r = (uint16_t)bn_apply2(d[u], k[u], relu);
-            }
-            yout[vi] = r;
+        const uint32_t off = vi < p.nvec ? vi * (2u * V) : kBnNoLoad;
+        const bool relu = p.relu != 0;
+        uint32_t r[NW];
+#pragma unroll
+        for (int i = 0; i < NW; ++i) r[i] = bn_apply2(d[u][i], k[u], relu);
+        if constexpr (V == 8) {
+            const bn_u32x4 o = {r[0], r[1], r[2], r[3]};
+            __builtin_amdgcn_raw_buffer_store_b128(o, ry, off, 0, 0);
+        } else if constexpr (V == 4) {
+            const bn_u32x2 o = {r[0], r[1]};
+            __builtin_amdgcn_raw_buffer_store_b64(o, ry, off, 0, 0);
+        } else if constexpr (V == 2) {
+            __builtin_amdgcn_raw_buffer_store_b32(r[0], ry, off, 0, 0);
+        } else {
+            __builtin_amdgcn_raw_buffer_store_b16((uint16_t)r[0], ry, off, 0, 0);
         }
     }
 }
