@@ -82,7 +82,7 @@ constexpr int igemm_w_units(int ks, int wm_blocks, int waves_m, int stage_waves,
     const int nw = stage_waves;
     const int rpw = 32 * wm_blocks * waves_m / nw;
     const int wch = rpw * npl * ks * ks;
-    return nw * ((wch + 63) / 64) * 64;
+    return nw * (((wch + 63) / 64) * 64 + (rpw == 8 ? 8 : 0));    // 8-row slices sit half a bank row apart
 }
 
 // One instantiation of the implicit-GEMM kernel.

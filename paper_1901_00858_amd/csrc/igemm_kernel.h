@@ -166,7 +166,10 @@ __global__ __launch_bounds__(64 * (WAVES_M * WAVES_N + PW)) void igemm_kernel(co
     constexpr int CPR = NPL * T;                 // 16-byte chunks per row per step
     constexpr int WCH = RPW * CPR;               // chunks (= LDS units) of one wave's rows
     constexpr int WLR = (WCH + 63) / 64;         // LDS-direct load rounds per lane
-    constexpr int WSL = WLR * 64;                // LDS units of one wave's slice (every lane of every round lands inside)
+    // LDS units of one wave's slice (every lane of every round lands inside).  Slices of 8 rows are
+    // 128 bytes per (tap, plane) and a 16-lane group of an operand read spans two of them: half a
+    // bank row apart (8 units more per slice) they do not collide.
+    constexpr int WSL = WLR * 64 + (RPW == 8 ? 8 : 0);
     constexpr int W_UNITS = NWS * WSL;
     constexpr int WIT = RPW * NPL;               // (row, plane) items per wave
     constexpr int WIR = (WIT + 63) / 64;
