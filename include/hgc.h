@@ -83,7 +83,8 @@ typedef struct hgc_plan {
     int32_t tile_m;          /* output channels per workgroup                           */
     int32_t tile_h, tile_w;  /* output pixels per workgroup and image: tile_h rows x tile_w
                                 cols (1x1 stride-1 unpadded layers: of the image seen as
-                                one row of H*W pixels)                                  */
+                                one row of H*W pixels; HGC_PATH_POINTWISE: tile_w pixels
+                                of all images' pixels taken as one axis)                */
     int32_t split_k;         /* >= 1; number of reduction slices                        */
     int32_t variant;         /* kernel instantiation index (diagnostic)                 */
     int32_t grid;            /* workgroups of the main kernel                           */
