@@ -120,6 +120,8 @@ __global__ __launch_bounds__(256) void depthwise3_vec_kernel(const ConvArgs p)
     const uint32_t lane = threadIdx.x & 63;
     const __amdgpu_buffer_rsrc_t rx =
         __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t *>(p.x), 0, p.x_bytes, 0x00020000);
+    const __amdgpu_buffer_rsrc_t rb = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<uint16_t *>(p.bias ? p.b : p.x), 0, p.bias ? 2 * p.M : 0, 0x00020000);
     for (uint32_t t = blockIdx.x * 256u + threadIdx.x; t - lane < items; t += gridDim.x * 256u) {
         const bool live = t < items;               // whole waves stay in the loop: shuffles need every lane
         const uint32_t tt = live ? t : items - 1;
@@ -131,7 +133,8 @@ __global__ __launch_bounds__(256) void depthwise3_vec_kernel(const ConvArgs p)
         float wr[9];
 #pragma unroll
         for (int k = 0; k < 9; ++k) wr[k] = h2f(p.w[(size_t)c * 9 + k]);
-        const float bv = p.bias ? h2f(p.b[c]) : 0.0f;
+        // range-checked (zero without a bias): no branch, no wait of its own
+        const float bv = h2f((uint16_t)__builtin_amdgcn_raw_buffer_load_b16(rb, 2u * (uint32_t)c, 0, 0));
         const int iw0 = owg * VI;                  // first input column of the vector; the window starts at iw0 - 1
         const uint32_t plane = 2u * nc * (uint32_t)(p.H * p.W);      // byte offset of the (n, c) plane
         // Every load of the item is issued before the first is used: the rows as range-checked buffer
@@ -194,11 +197,14 @@ __global__ __launch_bounds__(256) void depthwise3_vec_kernel(const ConvArgs p)
             // halo columns: the neighbour lane holds the adjacent vector of the same row
             float left = __shfl_up(in[VI], 1);
             float right = __shfl_down(in[1], 1);
-            if (owg == 0) left = 0.0f;             // padding column
-            else if (lane == 0) left = h2f((uint16_t)edge_l[rr]);
+            // selects, not branches: a load that is used only inside a branch is moved there
+            // and waited for on the spot, with every other load of the item
+            const float el = h2f((uint16_t)edge_l[rr]), er = h2f((uint16_t)edge_r[rr]);
+            left = lane == 0 ? el : left;
+            left = owg == 0 ? 0.0f : left;         // padding column
             if (STRIDE == 1) {
-                if (owg == (int)GW - 1) right = 0.0f;
-                else if (lane == 63) right = h2f((uint16_t)edge_r[rr]);
+                right = lane == 63 ? er : right;
+                right = owg == (int)GW - 1 ? 0.0f : right;
             }
             in[0] = left;
             in[VI + 1] = right;
@@ -277,9 +283,11 @@ hipError_t launch_depthwise(const ConvArgs &a, hipStream_t stream)
 
 // Sum the FP32 slices of a split reduction in slice order (deterministic), then
 // bias, ReLU and the one rounding to FP16.  The job is tiny and latency-bound: a thread
-// owns V consecutive outputs and has the loads of up to eight slices in flight at once
-// (the additions still happen in slice order).
-template <int V>
+// owns V consecutive outputs and has the loads of S slices in flight at once (the
+// additions still happen in slice order).  No load sits behind a branch, which would
+// give it a wait of its own: past the last slice the last one is read again and a zero
+// is added instead.
+template <int V, int S>
 __global__ __launch_bounds__(256) void splitk_reduce_kernel(const ConvArgs p)
 {
     typedef float fvec __attribute__((ext_vector_type(V)));
@@ -289,24 +297,29 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const ConvArgs p)
     if (o >= total) return;
     const fvec *src = reinterpret_cast<const fvec *>(p.ws + o);
     const size_t stride = (size_t)total / V;      // total % V == 0 (checked by the launcher)
+    const int last = p.split_k - 1;
+    // V consecutive outputs lie in one channel's plane when HoWo % V == 0 (checked by the launcher).
+    // The bias is fetched with the slices (from the workspace, ignored, when there is none).
+    const uint32_t m = ((uint32_t)o / (uint32_t)HoWo) % (uint32_t)p.M;
+    const uint16_t bias_raw = *(p.bias ? p.b + m : reinterpret_cast<const uint16_t *>(p.ws));
     float acc[V];
 #pragma unroll
     for (int v = 0; v < V; ++v) acc[v] = 0.0f;
-    for (int k0 = 0; k0 < p.split_k; k0 += 8) {
-        fvec part[8];
+    for (int k0 = 0; k0 < p.split_k; k0 += S) {
+        fvec part[S];
 #pragma unroll
-        for (int k = 0; k < 8; ++k)
-            if (k0 + k < p.split_k) part[k] = src[(size_t)(k0 + k) * stride];
+        for (int k = 0; k < S; ++k) part[k] = src[(size_t)min(k0 + k, last) * stride];
 #pragma unroll
-        for (int k = 0; k < 8; ++k)
-            if (k0 + k < p.split_k) {
+        for (int k = 0; k < S; ++k) {
+            const bool live = k0 + k <= last;
 #pragma unroll
-                for (int v = 0; v < V; ++v) acc[v] += V == 1 ? ((const float *)&part[k])[0] : part[k][v];
+            for (int v = 0; v < V; ++v) {
+                const float t = V == 1 ? ((const float *)&part[k])[0] : part[k][v];
+                acc[v] += live ? t : 0.0f;
             }
+        }
     }
-    // V consecutive outputs lie in one channel's plane when HoWo % V == 0 (checked by the launcher)
-    const int m = (int)((o / HoWo) % p.M);
-    const float bias = p.bias ? h2f(p.b[m]) : 0.0f;
+    const float bias = p.bias ? h2f(bias_raw) : 0.0f;
     uint16_t out[V];
 #pragma unroll
     for (int v = 0; v < V; ++v) {
@@ -323,17 +336,25 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const ConvArgs p)
     }
 }
 
+template <int V>
+static void launch_splitk_reduce_v(const ConvArgs &a, long long blocks, hipStream_t stream)
+{
+    if (a.split_k <= 2)
+        hipLaunchKernelGGL((splitk_reduce_kernel<V, 2>), dim3((unsigned)blocks), dim3(256), 0, stream, a);
+    else if (a.split_k <= 4)
+        hipLaunchKernelGGL((splitk_reduce_kernel<V, 4>), dim3((unsigned)blocks), dim3(256), 0, stream, a);
+    else
+        hipLaunchKernelGGL((splitk_reduce_kernel<V, 8>), dim3((unsigned)blocks), dim3(256), 0, stream, a);
+}
+
 hipError_t launch_splitk_reduce(const ConvArgs &a, hipStream_t stream)
 {
     const long long total = (long long)a.N * a.M * a.Ho * a.Wo;
     const bool vec = ((a.Ho * a.Wo) % 4 == 0) && (((uintptr_t)a.ws & 15) == 0) && (((uintptr_t)a.y & 7) == 0);
-    if (vec) {
-        const long long blocks = (total / 4 + 255) / 256;
-        hipLaunchKernelGGL(splitk_reduce_kernel<4>, dim3((unsigned)blocks), dim3(256), 0, stream, a);
-    } else {
-        const long long blocks = (total + 255) / 256;
-        hipLaunchKernelGGL(splitk_reduce_kernel<1>, dim3((unsigned)blocks), dim3(256), 0, stream, a);
-    }
+    if (vec)
+        launch_splitk_reduce_v<4>(a, (total / 4 + 255) / 256, stream);
+    else
+        launch_splitk_reduce_v<1>(a, (total + 255) / 256, stream);
     return hipGetLastError();
 }
 

@@ -428,11 +428,15 @@ __global__ __launch_bounds__(64 * (WAVES_M * WAVES_N + PW)) void igemm_kernel(co
     typedef float __attribute__((ext_vector_type(4), may_alias)) floatx4;
     constexpr int BROWS = (32 * A + 63) / 64;
     float bias_row[BROWS];
+    const __amdgpu_buffer_rsrc_t rb = make_rsrc(p.bias ? (const void *)p.b : (const void *)p.x, p.bias ? 2u * (uint32_t)p.M : 0u);
 #pragma unroll
     for (int r = 0; r < BROWS; ++r) {
         const int ml = m0 + wm * (32 * A) + lane + 64 * r;
-        bias_row[r] = (!SPLITK && p.bias && wave < NW && lane + 64 * r < 32 * A && ml < Mg)
-                          ? (float)__builtin_bit_cast(_Float16, p.b[g * Mg + ml]) : 0.0f;
+        // a range-checked load (zero where there is no bias or no such row): a load behind a
+        // branch would be waited for on the spot, ahead of the first patch loads
+        const bool want = !SPLITK && wave < NW && lane + 64 * r < 32 * A && ml < Mg;
+        const uint16_t raw = __builtin_amdgcn_raw_buffer_load_b16(rb, want ? 2u * (uint32_t)(g * Mg + ml) : kNoLoad, 0, 0);
+        bias_row[r] = (float)__builtin_bit_cast(_Float16, raw);
     }
     floatx16 acc[A][B];
     auto init_acc = [&]() {

@@ -69,10 +69,14 @@ __global__ __launch_bounds__(256) void smallc_kernel(const ConvArgs p)
     // bias of the wave's rows, fetched early (see init below)
     constexpr int BROWS = (BM + 63) / 64;
     float bias_row[BROWS];
+    const __amdgpu_buffer_rsrc_t rb = make_rsrc(p.bias ? (const void *)p.b : (const void *)p.x, p.bias ? 2u * (uint32_t)p.M : 0u);
 #pragma unroll
     for (int r = 0; r < BROWS; ++r) {
         const int ml = m0 + lane + 64 * r;
-        bias_row[r] = (p.bias && lane + 64 * r < BM && ml < p.M) ? (float)__builtin_bit_cast(_Float16, p.b[ml]) : 0.0f;
+        // range-checked (zero where there is no bias or no such row); no branch, no wait of its own
+        const bool want = lane + 64 * r < BM && ml < p.M;
+        const uint16_t raw = __builtin_amdgcn_raw_buffer_load_b16(rb, want ? 2u * (uint32_t)ml : kNoLoad, 0, 0);
+        bias_row[r] = (float)__builtin_bit_cast(_Float16, raw);
     }
 
     // ---- weights: LDS-direct loads of whole 64-unit runs, already in operand order ----
