@@ -347,7 +347,7 @@ static void make_plan(const Geometry &g0, bool with_ws, int x_align, bool w_al16
     const bool use_tuned = tuned && forced == HGC_PATH_AUTO && !fc.any();
     if (use_tuned) fc = *tuned;
     const bool depthwise_ok = (g.G == g.C && g.M == g.C && (g.k == 3 || g.k == 5));
-    const bool first_ok = packed && g.G == 1 && g.C <= 4 && (g.k == 3 || g.k == 5 || g.k == 7) && g.M >= 16;
+    const bool first_ok = packed && g.G == 1 && g.C <= 4 && (g.k == 3 || g.k == 5 || g.k == 7 || g.k == 11) && g.M >= 16;
 
     // 1x1 layers as a GEMM over all images' pixels: taken once the tiles fill most of the chip (below
     // that the implicit-GEMM kernels' reduction split keeps more compute units busy)

@@ -127,7 +127,7 @@ const IgemmVariant *igemm_variants_packed(int *count);
 struct PackedLayout {
     long long raw_bytes, igemm_off, zero_off, total;
     int MB8, NP8;
-    // first-layer section (one group, at most 4 input channels, k in {3, 5, 7}; else c4_off = 0):
+    // first-layer section (one group, at most 4 input channels, k in {3, 5, 7, 11}; else c4_off = 0):
     // 16-byte units [k rows][ceil(k/2) tap pairs][c4_mpad output channels] of
     // {tap 2qp: channels 0..3, tap 2qp+1: channels 0..3}, zero past C, k and M
     long long c4_off;

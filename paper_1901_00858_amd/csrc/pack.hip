@@ -21,7 +21,7 @@ PackedLayout packed_layout(const Geometry &g)
     pl.total = pl.zero_off + 1024;
     pl.c4_off = 0;
     pl.c4_mpad = 0;
-    if (g.G == 1 && g.Cg <= 4 && (g.k == 3 || g.k == 5 || g.k == 7)) {
+    if (g.G == 1 && g.Cg <= 4 && (g.k == 3 || g.k == 5 || g.k == 7 || g.k == 11)) {
         pl.c4_off = pl.total;
         pl.c4_mpad = (g.M + 63) / 64 * 64;
         const long long c4_units = (long long)g.k * ((g.k + 1) / 2) * pl.c4_mpad;

@@ -96,24 +96,39 @@ __global__ __launch_bounds__(256) void smallc_kernel(const ConvArgs p)
     const int ipr = PWU / XV;
     const int items = PH * ipr;
     const uint32_t img_off = 2u * (uint32_t)(n * p.C * HW);
-    for (int id = tid; id < items; id += 256) {
-        const int ph = (int)fast_div((uint32_t)id, p.fd_ipr), pd = id - ph * ipr;
-        const int ih = ih0 + ph, iw = iwa + pd * XV;
-        const bool inside = ih >= 0 && ih < p.H && iw >= 0 && iw < p.W;
-        const uint32_t vo = inside ? img_off + 2u * (uint32_t)(ih * p.W + iw) : kNoLoad;
-        uint32_t d[4];
+    // U items per thread and round, the loads of all of them issued before the first is stored (large
+    // kernels with a stride have patches of thousands of items: one round trip per item would dominate).
+    // An item past the end loads from an out-of-range offset and stores nothing.
+    constexpr int U = KS >= 7 ? 4 : 1;
+    for (int id0 = tid; id0 < items; id0 += 256 * U) {
+        uint32_t d[U][4];
+        int ph[U], pd[U];
 #pragma unroll
-        for (int c = 0; c < 4; ++c) {
-            const uint32_t vc = c < p.C ? vo : kNoLoad;
-            if (XV == 2) d[c] = __builtin_amdgcn_raw_buffer_load_b32(rx, vc, 2u * (uint32_t)(c * HW), 0);
-            else d[c] = (uint16_t)__builtin_amdgcn_raw_buffer_load_b16(rx, vc, 2u * (uint32_t)(c * HW), 0);
+        for (int u = 0; u < U; ++u) {
+            const int id = id0 + 256 * u;
+            ph[u] = (int)fast_div((uint32_t)id, p.fd_ipr);
+            pd[u] = id - ph[u] * ipr;
+            const int ih = ih0 + ph[u], iw = iwa + pd[u] * XV;
+            const bool inside = id < items && ih >= 0 && ih < p.H && iw >= 0 && iw < p.W;
+            const uint32_t vo = inside ? img_off + 2u * (uint32_t)(ih * p.W + iw) : kNoLoad;
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                const uint32_t vc = c < p.C ? vo : kNoLoad;
+                if (XV == 2) d[u][c] = __builtin_amdgcn_raw_buffer_load_b32(rx, vc, 2u * (uint32_t)(c * HW), 0);
+                else d[u][c] = (uint16_t)__builtin_amdgcn_raw_buffer_load_b16(rx, vc, 2u * (uint32_t)(c * HW), 0);
+            }
         }
-        if (XV == 2) {
-            const u32x4 v = {pack_lo(d[0], d[1]), pack_lo(d[2], d[3]), pack_hi(d[0], d[1]), pack_hi(d[2], d[3])};
-            *reinterpret_cast<u32x4_alias *>(xl + ph * PWU + pd * 2) = v;       // PWU is even: 16-byte aligned
-        } else {
-            const u32x2s v = {d[0] | (d[1] << 16), d[2] | (d[3] << 16)};
-            xl[ph * PWU + pd] = v;
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            if (id0 + 256 * u >= items) continue;
+            if (XV == 2) {
+                const u32x4 v = {pack_lo(d[u][0], d[u][1]), pack_lo(d[u][2], d[u][3]), pack_hi(d[u][0], d[u][1]),
+                                 pack_hi(d[u][2], d[u][3])};
+                *reinterpret_cast<u32x4_alias *>(xl + ph[u] * PWU + pd[u] * 2) = v;     // PWU is even: 16-byte aligned
+            } else {
+                const u32x2s v = {d[u][0] | (d[u][1] << 16), d[u][2] | (d[u][3] << 16)};
+                xl[ph[u] * PWU + pd[u]] = v;
+            }
         }
     }
 
@@ -216,6 +231,7 @@ hipError_t launch_smallc(const ConvArgs &a, int blocks_m, int xv, size_t lds, hi
     case 3: return launch_ks<3>(a, blocks_m, xv, lds, stream);
     case 5: return launch_ks<5>(a, blocks_m, xv, lds, stream);
     case 7: return launch_ks<7>(a, blocks_m, xv, lds, stream);
+    case 11: return launch_ks<11>(a, blocks_m, xv, lds, stream);
     default: return hipErrorInvalidValue;
     }
 }

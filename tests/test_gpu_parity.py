@@ -323,6 +323,9 @@ FIRST = [
     (2, 2, 9, 40, 70, 5, 2, 2),         # three M tiles of 32.., ragged everything
     (1, 3, 7, 7, 16, 7, 1, 3),          # kernel as large as the image
     (2, 3, 33, 66, 64, 3, 2, 0),        # no padding, stride 2
+    (1, 3, 227, 227, 96, 11, 4, 0),     # AlexNet conv1: 11x11 stride 4 (patches of thousands of items)
+    (2, 3, 64, 50, 40, 11, 4, 2),       # 11x11 with padding, ragged tiles, M = 40
+    (1, 1, 31, 31, 16, 11, 1, 5),       # 11x11 stride 1, one channel, odd width
 ]
 
 
