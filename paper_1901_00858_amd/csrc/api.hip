@@ -117,6 +117,7 @@ struct Plan {
     ConvArgs args;
     const IgemmVariant *variant;
     double cycles;       // the cost model's estimate (implicit-GEMM paths)
+    int first_packed;        // first-layer kernel: weights from the packed buffer's section (else the caller's layout)
     int first_a, first_xv;   // first-layer kernel: 32-row blocks per workgroup, input pixels per load;
                              // pointwise kernel: 64-row and 64-pixel blocks per workgroup
 };
@@ -347,7 +348,7 @@ static void make_plan(const Geometry &g0, bool with_ws, int x_align, bool w_al16
     const bool use_tuned = tuned && forced == HGC_PATH_AUTO && !fc.any();
     if (use_tuned) fc = *tuned;
     const bool depthwise_ok = (g.G == g.C && g.M == g.C && (g.k == 3 || g.k == 5));
-    const bool first_ok = packed && g.G == 1 && g.C <= 4 && (g.k == 3 || g.k == 5 || g.k == 7 || g.k == 11) && g.M >= 16;
+    const bool first_ok = g.G == 1 && g.C <= 4 && (g.k == 3 || g.k == 5 || g.k == 7 || g.k == 11) && g.M >= 16;
 
     // 1x1 layers as a GEMM over all images' pixels: taken once the tiles fill most of the chip (below
     // that the implicit-GEMM kernels' reduction split keeps more compute units busy)
@@ -413,7 +414,7 @@ static void make_plan(const Geometry &g0, bool with_ws, int x_align, bool w_al16
             a->log2_ti = 0;
             for (a->log2_thi = 0; (1 << a->log2_thi) < (BN >> a->log2_tw); ++a->log2_thi) {}
             a->fd_ipr = make_fastdiv((uint32_t)(a->PWU / xv)); a->fd_PH = make_fastdiv((uint32_t)a->PH);
-            pl->first_a = A; pl->first_xv = xv;
+            pl->first_a = A; pl->first_xv = xv; pl->first_packed = packed ? 1 : 0;
             pl->pub.path = HGC_PATH_FIRST_LAYER;
             pl->pub.tile_m = 32 * A; pl->pub.tile_w = 1 << a->log2_tw; pl->pub.tile_h = BN >> a->log2_tw;
             pl->pub.tile_n = 1;
@@ -538,7 +539,7 @@ static hipError_t enqueue(const Plan &pl, hipStream_t s)
         e = launch_depthwise(a, s);
         break;
     case HGC_PATH_FIRST_LAYER:
-        e = launch_smallc(a, pl.first_a, pl.first_xv, (size_t)pl.pub.lds_bytes, s);
+        e = launch_smallc(a, pl.first_a, pl.first_xv, (size_t)pl.pub.lds_bytes, pl.first_packed != 0, s);
         break;
     case HGC_PATH_POINTWISE:
         e = launch_pointwise(a, pl.first_a, pl.first_xv, s);

@@ -7,7 +7,8 @@
 // channels of one pixel, so the operand of a tap pair (r, 2*qp), (r, 2*qp+1) for a pixel is
 // the 16 bytes of two adjacent patch pixels: one read, whatever the stride.  The weights come
 // from the packed buffer's first-layer section (pack.hip): 16-byte units [tap row r][pair
-// qp][output channel] = {tap 2qp: c0..c3, tap 2qp+1: c0..c3}, zero past C, k and M.  The
+// qp][output channel] = {tap 2qp: c0..c3, tap 2qp+1: c0..c3}, zero past C, k and M; the
+// caller-layout form (PACKED = false) gathers the same units from w[m][c][r][q] itself.  The
 // whole reduction (k*ceil(k/2) units of 8) fits LDS at once, so there is no K loop: stage,
 // one barrier, MFMAs, epilogue.  Same arithmetic as everywhere: FP16 products, FP32
 // accumulation starting from the bias, one rounding (paper Sections 3.1 and 3.3).
@@ -23,7 +24,7 @@ typedef u32x2s __attribute__((may_alias)) u32x2_alias;
 
 // KS: kernel extent.  A: 32-row blocks of output channels (BM = 32*A), B: 32-pixel blocks per
 // wave; 4 waves along the pixels (BN = 128*B).  XV: input pixels per global load (2 or 1).
-template <int KS, int A, int B, int XV>
+template <int KS, int A, int B, int XV, bool PACKED>
 __global__ __launch_bounds__(256) void smallc_kernel(const ConvArgs p)
 {
     constexpr int NW = 4;
@@ -79,17 +80,49 @@ __global__ __launch_bounds__(256) void smallc_kernel(const ConvArgs p)
         bias_row[r] = (float)__builtin_bit_cast(_Float16, raw);
     }
 
-    // ---- weights: LDS-direct loads of whole 64-unit runs, already in operand order ----
-    constexpr int WROUNDS = (W_UNITS / 64 + NW - 1) / NW;
+    if constexpr (PACKED) {
+        // ---- weights: LDS-direct loads of whole 64-unit runs, already in operand order ----
+        constexpr int WROUNDS = (W_UNITS / 64 + NW - 1) / NW;
 #pragma unroll
-    for (int k = 0; k < WROUNDS; ++k) {
-        const int run = k * NW + wave;           // 64 units: BM/64... rows of one unit index (or two, BM = 32)
-        const int u = run * 64 + lane;
-        const int kg = u / BM, row = u % BM;
-        const bool real = (run * 64 < W_UNITS) && kg < NG;
-        const uint32_t vo = real ? p.wp_off + 16u * (uint32_t)(kg * p.MB8 + m0 + row) : p.wp_zero;
-        if (run * 64 < W_UNITS)
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(rw, (lds_ptr_t)(wl + run * 64), 16, vo, 0, 0, 0);
+        for (int k = 0; k < WROUNDS; ++k) {
+            const int run = k * NW + wave;       // 64 units: BM/64... rows of one unit index (or two, BM = 32)
+            const int u = run * 64 + lane;
+            const int kg = u / BM, row = u % BM;
+            const bool real = (run * 64 < W_UNITS) && kg < NG;
+            const uint32_t vo = real ? p.wp_off + 16u * (uint32_t)(kg * p.MB8 + m0 + row) : p.wp_zero;
+            if (run * 64 < W_UNITS)
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rw, (lds_ptr_t)(wl + run * 64), 16, vo, 0, 0, 0);
+        }
+    } else {
+        // ---- weights in the caller's layout w[m][c][r][q]: unit (r, qp, row) gathers taps (r, 2qp) and
+        // (r, 2qp+1) of its row's (up to) 4 channels, eight 2-byte range-checked loads (zero past C, k, M
+        // and for the padding unit); WU units per thread in flight at a time ----
+        constexpr int WU = 2;
+        for (int u0 = tid; u0 < W_UNITS; u0 += 256 * WU) {
+            uint32_t h[WU][8];
+#pragma unroll
+            for (int uu = 0; uu < WU; ++uu) {
+                const int u = u0 + 256 * uu;
+                const int kg = u / BM, row = u % BM;
+                const int r = kg / QP, qp = kg % QP, m = m0 + row;
+                const bool unit_ok = u < W_UNITS && kg < NG && m < p.M;
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    const int q = 2 * qp + (j >> 2), c = j & 3;
+                    const bool ok = unit_ok && c < p.C && q < KS;
+                    const uint32_t off = ok ? 2u * (uint32_t)(((m * p.C + c) * KS + r) * KS + q) : kNoLoad;
+                    h[uu][j] = (uint16_t)__builtin_amdgcn_raw_buffer_load_b16(rw, off, 0, 0);
+                }
+            }
+#pragma unroll
+            for (int uu = 0; uu < WU; ++uu) {
+                const int u = u0 + 256 * uu;
+                if (u >= W_UNITS) continue;
+                const u32x4 v = {h[uu][0] | (h[uu][1] << 16), h[uu][2] | (h[uu][3] << 16), h[uu][4] | (h[uu][5] << 16),
+                                 h[uu][6] | (h[uu][7] << 16)};
+                wl[u] = v;
+            }
+        }
     }
 
     // ---- input patch: XV pixels x 4 channels per item, transposed to pixel-major units ----
@@ -194,11 +227,11 @@ __global__ __launch_bounds__(256) void smallc_kernel(const ConvArgs p)
     store_tile<A, B>(p, acc, wl, wave, 0, wave, lane, n, 0, m0, oh0, ow0);
 }
 
-template <int KS, int A, int B, int XV>
+template <int KS, int A, int B, int XV, bool PACKED>
 static hipError_t launch_one(const ConvArgs &a, size_t lds, hipStream_t stream)
 {
     static std::atomic<size_t> granted{0};
-    auto kern = smallc_kernel<KS, A, B, XV>;
+    auto kern = smallc_kernel<KS, A, B, XV, PACKED>;
     if (lds > 64 * 1024 && lds > granted.load(std::memory_order_acquire)) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
@@ -209,11 +242,24 @@ static hipError_t launch_one(const ConvArgs &a, size_t lds, hipStream_t stream)
     return hipGetLastError();
 }
 
-template <int KS>
+template <int KS, bool PACKED>
 static hipError_t launch_ks(const ConvArgs &a, int blocks_m, int xv, size_t lds, hipStream_t s)
 {
-    if (blocks_m == 2) return xv == 2 ? launch_one<KS, 2, 2, 2>(a, lds, s) : launch_one<KS, 2, 2, 1>(a, lds, s);
-    return xv == 2 ? launch_one<KS, 1, 2, 2>(a, lds, s) : launch_one<KS, 1, 2, 1>(a, lds, s);
+    if (blocks_m == 2)
+        return xv == 2 ? launch_one<KS, 2, 2, 2, PACKED>(a, lds, s) : launch_one<KS, 2, 2, 1, PACKED>(a, lds, s);
+    return xv == 2 ? launch_one<KS, 1, 2, 2, PACKED>(a, lds, s) : launch_one<KS, 1, 2, 1, PACKED>(a, lds, s);
+}
+
+template <bool PACKED>
+static hipError_t launch_layout(const ConvArgs &a, int blocks_m, int xv, size_t lds, hipStream_t stream)
+{
+    switch (a.ks) {
+    case 3: return launch_ks<3, PACKED>(a, blocks_m, xv, lds, stream);
+    case 5: return launch_ks<5, PACKED>(a, blocks_m, xv, lds, stream);
+    case 7: return launch_ks<7, PACKED>(a, blocks_m, xv, lds, stream);
+    case 11: return launch_ks<11, PACKED>(a, blocks_m, xv, lds, stream);
+    default: return hipErrorInvalidValue;
+    }
 }
 
 long long smallc_lds_bytes(int ks, int blocks_m, int PH, int PWU)
@@ -225,15 +271,9 @@ long long smallc_lds_bytes(int ks, int blocks_m, int PH, int PWU)
     return bias + (main > epi ? main : epi);
 }
 
-hipError_t launch_smallc(const ConvArgs &a, int blocks_m, int xv, size_t lds, hipStream_t stream)
+hipError_t launch_smallc(const ConvArgs &a, int blocks_m, int xv, size_t lds, bool packed, hipStream_t stream)
 {
-    switch (a.ks) {
-    case 3: return launch_ks<3>(a, blocks_m, xv, lds, stream);
-    case 5: return launch_ks<5>(a, blocks_m, xv, lds, stream);
-    case 7: return launch_ks<7>(a, blocks_m, xv, lds, stream);
-    case 11: return launch_ks<11>(a, blocks_m, xv, lds, stream);
-    default: return hipErrorInvalidValue;
-    }
+    return packed ? launch_layout<true>(a, blocks_m, xv, lds, stream) : launch_layout<false>(a, blocks_m, xv, lds, stream);
 }
 
 }  // namespace hgc

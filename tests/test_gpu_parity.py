@@ -334,12 +334,14 @@ def test_first_layer_kernel(oracle, t):
     N, C, H, W, M, k, s, p = t
     for bias, relu in ((1, 1), (0, 0)):
         L = ConvLayer("first", N, C, H, W, M, k, s, p, 1, bias, relu)
-        plan = hgc.conv2d_plan(L, True, True).as_dict()
-        assert plan["path"] == hgc.PATH_FIRST_LAYER, plan
-        say(f"[first layer] {L} plan={plan}")
         x, w, b = make_tensors(L, seed=40 + k)
-        y = run_layer(L, x, w, b, use_ws=True, packed=True)
-        assert_full(oracle, L, x, w, b, y, tag="first layer")
+        # weights from the packed buffer's section, and gathered from the caller's layout
+        for ws, packed in ((True, True), (True, False), (False, False)):
+            plan = hgc.conv2d_plan(L, ws, packed).as_dict()
+            assert plan["path"] == hgc.PATH_FIRST_LAYER, plan
+            say(f"[first layer] {L} ws={ws} packed={packed} plan={plan}")
+            y = run_layer(L, x, w, b, use_ws=ws, packed=packed)
+            assert_full(oracle, L, x, w, b, y, tag=f"first layer packed={packed}")
 
 
 def test_first_layer_kernel_integer_exact_and_unaligned_input(oracle):
