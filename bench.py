@@ -26,9 +26,9 @@ PEAK_HBM = 8.0e12             # MI355X HBM3E B/s
 TRAFFIC_BYTES_PER_LAUNCH = {
     # mean over the kernel's launches of a step: FETCH_SIZE KiB x 2.0 (copy calibration) + WRITE_SIZE KiB x 1.0
     # N=1: conv5..conv8 (three launches of grid 224, one of grid 112)
-    ("vgg16", 1, "packed", "igemm", 26): int((2.0 * (3 * 5049.2 + 8712.0) / 4 + (3 * 1696.0 + 784.0) / 4) * 1024),
+    ("vgg16", 1, "packed", "igemm", 26): int((2.0 * (3 * 5050.2 + 8713.0) / 4 + (3 * 1696.0 + 784.0) / 4) * 1024),
     # N=16: conv3, conv4 (grid 448) and conv5..conv7 (grid 256)
-    ("vgg16", 16, "packed", "igemm", 0): int((2.0 * (2 * 20905.1 + 3 * 14462.9) / 5 + (2 * 53069.7 + 3 * 29312.3) / 5) * 1024),
+    ("vgg16", 16, "packed", "igemm", 0): int((2.0 * (2 * 20905.5 + 3 * 14462.8) / 5 + (2 * 52749.8 + 3 * 29187.5) / 5) * 1024),
 }
 
 
