@@ -55,6 +55,15 @@ __global__ __launch_bounds__(256) void inner_product_kernel(const IpArgs p)
     for (int r = 0; r < R; ++r)
 #pragma unroll
         for (int i = 0; i < NB; ++i) acc[r][i] = 0.0f;
+    // the rows' bias, fetched ahead of the reduction (range-checked: zero without a bias or past M);
+    // loaded in the epilogue it would be a round trip of its own at the end of every wave
+    const __amdgpu_buffer_rsrc_t rb = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<uint16_t *>(p.bias ? p.b : p.w), 0, p.bias ? 2 * p.M : 0, 0x00020000);
+    float bias_row[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r)
+        bias_row[r] = (float)__builtin_bit_cast(
+            _Float16, (uint16_t)__builtin_amdgcn_raw_buffer_load_b16(rb, m0 + r < p.M ? 2u * (uint32_t)(m0 + r) : 0xFFFFFFFFu, 0, 0));
 
     if (VEC) {
         // buffer loads: rows past M and images past N use an out-of-range offset and read zero
@@ -114,7 +123,7 @@ __global__ __launch_bounds__(256) void inner_product_kernel(const IpArgs p)
         for (int r = 0; r < R; ++r) {
             const int m = m0 + r;
             if (m >= p.M) continue;
-            const float bv = p.bias ? (float)__builtin_bit_cast(_Float16, p.b[m]) : 0.0f;
+            const float bv = bias_row[r];
 #pragma unroll
             for (int i = 0; i < NB; ++i) {
                 const int n = p.n0 + i;
