@@ -9,7 +9,7 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libhgc.so")
-SOURCES = ["api.hip", "igemm_raw.hip", "igemm_packed.hip", "direct.hip", "pack.hip", "inner_product.hip", "smallc.hip",
+SOURCES = ["api.hip", "igemm_tables.hip", *["igemm_%s_%d.hip" % (k, i) for k in ("raw", "packed") for i in range(4)], "direct.hip", "pack.hip", "inner_product.hip", "smallc.hip",
            "batch_norm.hip", "max_pool.hip", "pointwise.hip"]
 HEADERS = [os.path.join(CSRC, "hgc_internal.h"), os.path.join(CSRC, "igemm_kernel.h"), os.path.join(CSRC, "tile_store.h"),
            os.path.join(ROOT, "include", "hgc.h")]

@@ -1,5 +1,5 @@
 // Implicit-GEMM convolution forward on FP16 MFMA for gfx950: the kernel template and
-// its instantiation table.  Included by igemm_raw.hip and igemm_packed.hip, which set
+// its instantiation table.  Included by igemm_raw_<part>.hip and igemm_packed_<part>.hip, which set
 // HGC_IGEMM_PACKED (0: weights in the caller's layout, 1: pre-packed weights) and
 // HGC_IGEMM_ACCESSOR (the name of the function that returns the table).
 //
@@ -784,19 +784,24 @@ static hipError_t launch_igemm(const ConvArgs &a, size_t lds, hipStream_t stream
 #define HGC_VR(KS, A, B, WM, WN, NPL, NST, R2, R1)                                              \
     HGC_V1(KS, A, B, WM, WN, NPL, 2, 0, NST, R2), HGC_V1(KS, A, B, WM, WN, NPL, 1, 0, NST, R1)
 
+// The table is compiled in four parts (HGC_IGEMM_PART 0..3, one translation unit each, so that the
+// build uses several cores); igemm_tables.hip joins them in this order, which fixes the variant numbers.
 static const IgemmVariant g_variants[] = {
     //     KS  A  B  WM WN NPL NST  patch rounds in registers per input-load width
+#if HGC_IGEMM_PART == 0
     HGC_VX(3, 2, 4, 2, 4, 2, 2, 1, 1, 2, 2),    // 128 ch x 512 px, 8 waves: throughput tile
     HGC_VX(3, 4, 2, 2, 4, 2, 2, 1, 1, 1, 2),    // 256 ch x 256 px, 8 waves
     HGC_VX(3, 2, 4, 2, 2, 2, 2, 1, 2, 2, 4),    // 128 ch x 256 px
     HGC_VX(3, 2, 2, 2, 2, 2, 2, 1, 1, 2, 2),    // 128 ch x 128 px
     HGC_VX(3, 2, 2, 1, 4, 2, 2, 1, 1, 2, 4),    //  64 ch x 256 px
+#elif HGC_IGEMM_PART == 1
     HGC_VR(3, 2, 2, 1, 4, 2, 2, 2, 4),
     HGC_VX(3, 2, 1, 1, 4, 4, 2, 1, 1, 2, 2),    //  64 ch x 128 px, 32 channels per step
     HGC_VX(3, 1, 2, 2, 2, 4, 2, 1, 1, 2, 2),    //  64 ch x 128 px, waves 2 x 2
     HGC_VX(3, 1, 2, 1, 4, 2, 2, 1, 1, 2, 4),    //  32 ch x 256 px
     HGC_VX(3, 1, 1, 1, 4, 4, 2, 1, 1, 2, 2),    //  32 ch x 128 px, 32 channels per step
     HGC_VR(3, 1, 2, 1, 4, 2, 2, 2, 4),
+#elif HGC_IGEMM_PART == 2
     HGC_VX(1, 2, 4, 2, 2, 8, 2, 1, 1, 2, 4),    // pointwise 128 ch x 256 px, 64 channels per step
     HGC_VX(1, 2, 2, 1, 4, 8, 2, 1, 1, 2, 4),    // pointwise  64 ch x 256 px
     HGC_VR(1, 2, 2, 1, 4, 8, 2, 2, 4),
@@ -811,6 +816,7 @@ static const IgemmVariant g_variants[] = {
     HGC_VX(5, 2, 2, 1, 4, 2, 1, 1, 2, 3, 4),    // 5x5  64 ch x 256 px
     HGC_VR(5, 2, 2, 1, 4, 2, 1, 3, 4),
     HGC_VR(7, 1, 2, 1, 4, 2, 1, 3, 6),          // stem-like 7x7: 32 ch x 256 px
+#elif HGC_IGEMM_PART == 3
     // small tiles with the loads two steps ahead (three weight buffers): few, latency-bound workgroups
     HGC_VX(3, 1, 1, 1, 4, 4, 3, 1, 1, 2, 2),    //  32 ch x 128 px, 32 channels per step
     HGC_VX(3, 1, 1, 1, 4, 2, 3, 1, 1, 1, 2),    //  32 ch x 128 px, 16 channels per step
@@ -822,6 +828,9 @@ static const IgemmVariant g_variants[] = {
     HGC_VS(3, 2, 1, 1, 4, 4, 4, 1, 2, 2),       //  64 ch x 128 px, 32 channels per step
     HGC_VS(3, 1, 2, 1, 4, 2, 4, 1, 2, 4),       //  32 ch x 256 px, 16 channels per step
     HGC_VS(3, 1, 2, 1, 4, 4, 4, 2, 4, 4),       //  32 ch x 256 px, 32 channels per step
+#else
+#error "HGC_IGEMM_PART must be 0..3"
+#endif
 };
 
 const IgemmVariant *HGC_IGEMM_ACCESSOR(int *count)
