@@ -26,9 +26,9 @@ PEAK_HBM = 8.0e12             # MI355X HBM3E B/s
 TRAFFIC_BYTES_PER_LAUNCH = {
     # mean over the kernel's launches of a step: FETCH_SIZE KiB x 2.0 (copy calibration) + WRITE_SIZE KiB x 1.0
     # N=1: conv5..conv8 (three launches of grid 224, one of grid 112)
-    ("vgg16", 1, "packed", "igemm", 26): int((2.0 * (3 * 5050.2 + 8713.0) / 4 + (3 * 1696.0 + 784.0) / 4) * 1024),
+    ("vgg16", 1, "packed", "igemm", 82): int((2.0 * (3 * 5049.2 + 8712.0) / 4 + (3 * 1696.0 + 784.0) / 4) * 1024),
     # N=16: conv3, conv4 (grid 448) and conv5..conv7 (grid 256)
-    ("vgg16", 16, "packed", "igemm", 0): int((2.0 * (2 * 20905.5 + 3 * 14462.8) / 5 + (2 * 52749.8 + 3 * 29187.5) / 5) * 1024),
+    ("vgg16", 16, "packed", "igemm", 0): int((2.0 * (2 * 20920.1 + 3 * 14477.4) / 5 + (2 * 53000.7 + 3 * 29103.7) / 5) * 1024),
 }
 
 
@@ -130,19 +130,22 @@ def main() -> int:
     bytes_step = sum(L.bytes for L in layers)
     tflops = flops_step / (ms_per_step * 1e-3) / 1e12
 
-    # ---- per-launch device time: a pair of HIP events on the launch stream around EVERY
-    # launch of an instrumented pass (the timed region above carries no events) ----
+    # ---- per-launch device time: an instrumented pass (the timed region above carries no events) runs
+    # every layer `reps` times back to back between one pair of HIP events on the launch stream; the
+    # average is the launch's duration including the dispatch gap to the next launch, as in the timed
+    # chain.  (An event pair around each single launch adds the events' own gaps: two of them for a layer
+    # with a split reduction, which is two kernels.) ----
     reps = max(5, min(50, args.steps))
     per_layer = []
     for i, L in enumerate(layers):
         launch(i)
-        pairs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
-        for e0, e1 in pairs:
-            e0.record(stream)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        for _ in range(reps):
             launch(i)
-            e1.record(stream)
-        pairs[-1][1].synchronize()
-        us = sum(e0.elapsed_time(e1) for e0, e1 in pairs) * 1e3 / reps
+        e1.record(stream)
+        e1.synchronize()
+        us = e0.elapsed_time(e1) * 1e3 / reps
         plan = hgc.conv2d_plan(L, args.entry != "plain", args.entry == "packed").as_dict()
         per_layer.append({
             "layer": L.name, "path": plan["path_name"], "variant": plan["variant"],
