@@ -273,6 +273,9 @@ static bool plan_igemm(const Geometry &g, bool with_ws, int x_align, bool w_al16
                 int lth = 0;
                 while ((1 << lth) < TH) ++lth;
                 c.log2_thi = lth;
+                // a one-row map (every 1x1 stride-1 layer is flattened to one) has nothing for further window
+                // rows: they would only multiply the workgroups, each with the whole weight tile to fetch
+                if (g.Ho == 1 && TH > 1 && f_tw < 0) continue;
                 // more images per tile only where the map is small: at most about two windows of this size
                 if (ti > 0 && f_ti < 0 && (long long)(2 * TH) * TW <= (long long)g.Ho * g.Wo) continue;
                 c.tiles_w = ceil_div(g.Wo, TW);
