@@ -27,8 +27,10 @@ TRAFFIC_BYTES_PER_LAUNCH = {
     # mean over the kernel's launches of a step: FETCH_SIZE KiB x 2.0 (copy calibration) + WRITE_SIZE KiB x 1.0
     # N=1: conv5..conv8 (three launches of grid 224, one of grid 112)
     ("vgg16", 1, "packed", "igemm", 82): int((2.0 * (3 * 5049.2 + 8712.0) / 4 + (3 * 1696.0 + 784.0) / 4) * 1024),
+    # N=16: conv2 (grid 3136) and conv8..conv10 (grid 512)
+    ("vgg16", 16, "packed", "igemm", 12): int((2.0 * (50960.9 + 3 * 20712.3) / 4 + (100876.7 + 3 * 12544.5) / 4) * 1024),
     # N=16: conv3, conv4 (grid 448) and conv5..conv7 (grid 256)
-    ("vgg16", 16, "packed", "igemm", 0): int((2.0 * (2 * 20920.1 + 3 * 14477.4) / 5 + (2 * 53000.7 + 3 * 29103.7) / 5) * 1024),
+    ("vgg16", 16, "packed", "igemm", 0): int((2.0 * (2 * 20920.2 + 3 * 14477.3) / 5 + (2 * 52931.6 + 3 * 29106.3) / 5) * 1024),
 }
 
 
