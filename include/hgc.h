@@ -164,7 +164,7 @@ hgc_status hgc_conv2d_forward_packed(const hgc_conv2d_desc *desc, const void *x,
  * WAITS for the stream.  y and the workspace are overwritten; on return y holds the
  * layer's output.  chosen_out (may be NULL) receives the shape now in effect.  Same
  * errors, in the same order, as the forward call it tunes.  Descriptors that do not take
- * the implicit-GEMM path are left alone.  hgc_conv2d_tune_reset forgets every
+ * the implicit-GEMM path have nothing to measure: the layer is enqueued once as planned.  hgc_conv2d_tune_reset forgets every
  * remembered shape.  Both are thread-safe.
  */
 hgc_status hgc_conv2d_tune(const hgc_conv2d_desc *desc, const void *x, const void *w, const void *b, void *y,

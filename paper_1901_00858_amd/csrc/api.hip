@@ -581,8 +581,11 @@ static hgc_status tune(const hgc_conv2d_desc *desc, const void *x, const void *w
     hgc_status st = prepare(desc, x, w, b, y, ws, ws_bytes, true, packed, nullptr, &base);
     if (st != HGC_OK) return st;
     if (chosen) *chosen = base.pub;
-    if (base.pub.path != HGC_PATH_IGEMM && base.pub.path != HGC_PATH_IGEMM_SPLITK) return HGC_OK;
-    if (g_forced_path.load(std::memory_order_relaxed) != HGC_PATH_AUTO) return HGC_OK;
+    // nothing to measure (another path, or a test control is active): the layer is run once as planned,
+    // so that y holds its output on return in every case
+    if ((base.pub.path != HGC_PATH_IGEMM && base.pub.path != HGC_PATH_IGEMM_SPLITK) ||
+        g_forced_path.load(std::memory_order_relaxed) != HGC_PATH_AUTO)
+        return enqueue(base, s) == hipSuccess ? HGC_OK : HGC_ERR_LAUNCH;
     int x_align = 16;
     while (x_align > 2 && ((uintptr_t)x % x_align)) x_align >>= 1;
     const bool w_al16 = ((uintptr_t)w & 15) == 0;

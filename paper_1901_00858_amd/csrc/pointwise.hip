@@ -277,11 +277,17 @@ bool pointwise_eligible(const ConvArgs &c, int x_align, int y_align, bool w_al16
            x_align % 16 == 0 && y_align % 16 == 0 && c.M >= 32;
 }
 
+// below this many 128-row x 128-pixel tiles a layer takes 64-row tiles (measured: batch-1 stacks of ResNet-50 and
+// MobileNet-v1 shapes 6 % and 10 % faster with 64 and with 160; 256 and 400 cost the large batches 1-2 %)
+constexpr long long kPwSmallGrid = 160;
+
 void pointwise_tile(const ConvArgs &c, int *a, int *b)
 {
     // the larger tile once it still leaves every compute unit more than one workgroup
     const long long Q = (long long)c.N * c.H * c.W;
     *a = c.M <= 64 ? 1 : 2;                         // 64 rows a workgroup when there are no more
+    // ... or when 128-row tiles would leave most compute units without a workgroup
+    if (*a == 2 && ((c.M + 127) / 128) * ((Q + 127) / 128) < kPwSmallGrid) *a = 1;
     const long long big = ((c.M + 64 * *a - 1) / (64 * *a)) * ((Q + 255) / 256);
     *b = big >= 512 ? 4 : 2;
     // 256 rows x 128 pixels re-read x half as often from L2; measured to pay from about 1.5 workgroups per compute unit on
