@@ -280,6 +280,9 @@ bool pointwise_eligible(const ConvArgs &c, int x_align, int y_align, bool w_al16
 // below this many 128-row x 128-pixel tiles a layer takes 64-row tiles (measured: batch-1 stacks of ResNet-50 and
 // MobileNet-v1 shapes 6 % and 10 % faster with 64 and with 160; 256 and 400 cost the large batches 1-2 %)
 constexpr long long kPwSmallGrid = 160;
+// below this many 64-row x 128-pixel tiles a layer takes 64-pixel tiles (measured: the same batch-1 stacks another 11 %
+// faster with 128; 48 gains less, 256 and 512 cost ResNet-50 shapes at batch 32 half a percent)
+constexpr long long kPwTinyGrid = 128;
 
 void pointwise_tile(const ConvArgs &c, int *a, int *b)
 {
@@ -290,6 +293,8 @@ void pointwise_tile(const ConvArgs &c, int *a, int *b)
     if (*a == 2 && ((c.M + 127) / 128) * ((Q + 127) / 128) < kPwSmallGrid) *a = 1;
     const long long big = ((c.M + 64 * *a - 1) / (64 * *a)) * ((Q + 255) / 256);
     *b = big >= 512 ? 4 : 2;
+    // 64-pixel tiles when even the 64-row x 128-pixel tiles are few
+    if (*a == 1 && ((c.M + 63) / 64) * ((Q + 127) / 128) < kPwTinyGrid) *b = 1;
     // 256 rows x 128 pixels re-read x half as often from L2; measured to pay from about 1.5 workgroups per compute unit on
     if (*b == 2 && c.M >= 256 && ((c.M + 255) / 256) * ((Q + 127) / 128) >= 384) *a = 4;
 }
@@ -310,7 +315,7 @@ hipError_t launch_pointwise(const ConvArgs &c, int a, int b, hipStream_t s)
     p.tiles = (uint32_t)(p.tiles_m * ((p.Q + TP - 1) / TP));
     const unsigned blocks = (p.tiles + 7u) / 8u * 8u;
     const int v = p.P % 8 == 0 ? 8 : 4;
-    if (a == 1) return b == 4 ? pw_launch<1, 4>(p, v, blocks, s) : pw_launch<1, 2>(p, v, blocks, s);
+    if (a == 1) return b == 4 ? pw_launch<1, 4>(p, v, blocks, s) : b == 1 ? pw_launch<1, 1>(p, v, blocks, s) : pw_launch<1, 2>(p, v, blocks, s);
     if (a == 4) return pw_launch<4, 2>(p, v, blocks, s);
     return b == 4 ? pw_launch<2, 4>(p, v, blocks, s) : pw_launch<2, 2>(p, v, blocks, s);
 }

@@ -35,6 +35,7 @@ SHAPES = [
     (84, 64, 28, 28, 128),      # 65856 pixels: enough tiles for the wide (256-pixel) tile
     (42, 32, 56, 56, 64),       # the wide tile with 64 rows a workgroup (M <= 64), a single stage
     (32, 64, 28, 28, 300),      # 256 rows a workgroup, the second row tile ragged
+    (8, 64, 56, 56, 64),        # 64 rows x 128 pixels a workgroup (the small shapes above take 64 x 64 tiles)
 ]
 
 
