@@ -111,6 +111,7 @@ static Geometry kernel_geometry(const Geometry &g)
 }
 
 constexpr long long kPointwiseMinBlocks = 12;
+constexpr long long kFirstSmallGrid = 256;   // one workgroup per compute unit
 
 struct Plan {
     hgc_plan pub;
@@ -118,6 +119,7 @@ struct Plan {
     const IgemmVariant *variant;
     double cycles;       // the cost model's estimate (implicit-GEMM paths)
     int first_packed;        // first-layer kernel: weights from the packed buffer's section (else the caller's layout)
+    int first_b;             // first-layer kernel: 32-pixel blocks per wave (2 or 1)
     int first_a, first_xv;   // first-layer kernel: 32-row blocks per workgroup, input pixels per load;
                              // pointwise kernel: 64-row and 64-pixel blocks per workgroup
 };
@@ -392,7 +394,9 @@ static void make_plan(const Geometry &g0, bool with_ws, int x_align, bool w_al16
         // 32 or 64 channels x 256 pixels per workgroup; the window that wastes the fewest pixels,
         // then the smallest halo patch
         ConvArgs *a = &pl->args;
-        const int A = g.M > 32 ? 2 : 1, BN = 256;
+        // 256 pixels per workgroup, 128 when that leaves most compute units without one
+        const int A = g.M > 32 ? 2 : 1;
+        const int BN = (long long)ceil_div(g.M, 32 * A) * ceil_div((long long)g.Ho * g.Wo, 256) * g.N < kFirstSmallGrid ? 128 : 256;
         const int xv = (g.W % 2 == 0 && x_align % 4 == 0) ? 2 : 1;
         long long best_cost = -1;
         for (int j = 3; j <= 6; ++j) {
@@ -419,7 +423,7 @@ static void make_plan(const Geometry &g0, bool with_ws, int x_align, bool w_al16
             a->log2_ti = 0;
             for (a->log2_thi = 0; (1 << a->log2_thi) < (BN >> a->log2_tw); ++a->log2_thi) {}
             a->fd_ipr = make_fastdiv((uint32_t)(a->PWU / xv)); a->fd_PH = make_fastdiv((uint32_t)a->PH);
-            pl->first_a = A; pl->first_xv = xv; pl->first_packed = packed ? 1 : 0;
+            pl->first_a = A; pl->first_xv = xv; pl->first_packed = packed ? 1 : 0; pl->first_b = BN / 128;
             pl->pub.path = HGC_PATH_FIRST_LAYER;
             pl->pub.tile_m = 32 * A; pl->pub.tile_w = 1 << a->log2_tw; pl->pub.tile_h = BN >> a->log2_tw;
             pl->pub.tile_n = 1;
@@ -544,7 +548,7 @@ static hipError_t enqueue(const Plan &pl, hipStream_t s)
         e = launch_depthwise(a, s);
         break;
     case HGC_PATH_FIRST_LAYER:
-        e = launch_smallc(a, pl.first_a, pl.first_xv, (size_t)pl.pub.lds_bytes, pl.first_packed != 0, s);
+        e = launch_smallc(a, pl.first_a, pl.first_b, pl.first_xv, (size_t)pl.pub.lds_bytes, pl.first_packed != 0, s);
         break;
     case HGC_PATH_POINTWISE:
         e = launch_pointwise(a, pl.first_a, pl.first_xv, s);

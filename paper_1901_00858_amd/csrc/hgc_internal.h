@@ -150,10 +150,12 @@ hipError_t launch_direct(const ConvArgs &a, hipStream_t stream);
 hipError_t launch_depthwise(const ConvArgs &a, hipStream_t stream);
 hipError_t launch_splitk_reduce(const ConvArgs &a, hipStream_t stream);
 // first-layer kernel (smallc.hip): blocks_m = 32-row blocks of output channels per workgroup (1 or 2),
+// blocks_n = 32-pixel blocks per wave (2 or 1: 256 or 128 pixels per workgroup),
 // xv = input pixels per load (2 or 1); packed: a.wp_off = byte offset of the first-layer section, a.MB8 = c4_mpad
 // (else a.w is the caller's layout),
 // a.PWU = pixels per patch row (even)
 long long smallc_lds_bytes(int ks, int blocks_m, int PH, int PWU);
-hipError_t launch_smallc(const ConvArgs &a, int blocks_m, int xv, size_t lds, bool packed, hipStream_t stream);
+hipError_t launch_smallc(const ConvArgs &a, int blocks_m, int blocks_n, int xv, size_t lds, bool packed,
+                         hipStream_t stream);
 
 }  // namespace hgc

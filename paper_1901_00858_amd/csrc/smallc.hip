@@ -242,22 +242,22 @@ static hipError_t launch_one(const ConvArgs &a, size_t lds, hipStream_t stream)
     return hipGetLastError();
 }
 
-template <int KS, bool PACKED>
+template <int KS, int B, bool PACKED>
 static hipError_t launch_ks(const ConvArgs &a, int blocks_m, int xv, size_t lds, hipStream_t s)
 {
     if (blocks_m == 2)
-        return xv == 2 ? launch_one<KS, 2, 2, 2, PACKED>(a, lds, s) : launch_one<KS, 2, 2, 1, PACKED>(a, lds, s);
-    return xv == 2 ? launch_one<KS, 1, 2, 2, PACKED>(a, lds, s) : launch_one<KS, 1, 2, 1, PACKED>(a, lds, s);
+        return xv == 2 ? launch_one<KS, 2, B, 2, PACKED>(a, lds, s) : launch_one<KS, 2, B, 1, PACKED>(a, lds, s);
+    return xv == 2 ? launch_one<KS, 1, B, 2, PACKED>(a, lds, s) : launch_one<KS, 1, B, 1, PACKED>(a, lds, s);
 }
 
-template <bool PACKED>
+template <int B, bool PACKED>
 static hipError_t launch_layout(const ConvArgs &a, int blocks_m, int xv, size_t lds, hipStream_t stream)
 {
     switch (a.ks) {
-    case 3: return launch_ks<3, PACKED>(a, blocks_m, xv, lds, stream);
-    case 5: return launch_ks<5, PACKED>(a, blocks_m, xv, lds, stream);
-    case 7: return launch_ks<7, PACKED>(a, blocks_m, xv, lds, stream);
-    case 11: return launch_ks<11, PACKED>(a, blocks_m, xv, lds, stream);
+    case 3: return launch_ks<3, B, PACKED>(a, blocks_m, xv, lds, stream);
+    case 5: return launch_ks<5, B, PACKED>(a, blocks_m, xv, lds, stream);
+    case 7: return launch_ks<7, B, PACKED>(a, blocks_m, xv, lds, stream);
+    case 11: return launch_ks<11, B, PACKED>(a, blocks_m, xv, lds, stream);
     default: return hipErrorInvalidValue;
     }
 }
@@ -271,9 +271,14 @@ long long smallc_lds_bytes(int ks, int blocks_m, int PH, int PWU)
     return bias + (main > epi ? main : epi);
 }
 
-hipError_t launch_smallc(const ConvArgs &a, int blocks_m, int xv, size_t lds, bool packed, hipStream_t stream)
+hipError_t launch_smallc(const ConvArgs &a, int blocks_m, int blocks_n, int xv, size_t lds, bool packed,
+                         hipStream_t stream)
 {
-    return packed ? launch_layout<true>(a, blocks_m, xv, lds, stream) : launch_layout<false>(a, blocks_m, xv, lds, stream);
+    if (blocks_n == 1)
+        return packed ? launch_layout<1, true>(a, blocks_m, xv, lds, stream)
+                      : launch_layout<1, false>(a, blocks_m, xv, lds, stream);
+    return packed ? launch_layout<2, true>(a, blocks_m, xv, lds, stream)
+                  : launch_layout<2, false>(a, blocks_m, xv, lds, stream);
 }
 
 }  // namespace hgc
