@@ -357,8 +357,9 @@ static void make_plan(const Geometry &g0, bool with_ws, int x_align, bool w_al16
     const bool first_ok = g.G == 1 && g.C <= 4 && (g.k == 3 || g.k == 5 || g.k == 7 || g.k == 11) && g.M >= 16;
 
     // 1x1 layers as a GEMM over all images' pixels: taken from a dozen tiles on (measured on the 1x1 layers
-    // of ResNet-50- and MobileNet-v1-shaped stacks at batch 1: with 8 it was slower, with 24 too); with
-    // fewer tiles the implicit-GEMM kernels' reduction split keeps more compute units busy
+    // of ResNet-50- and MobileNet-v1-shaped stacks at batch 1: 24 and 48 were slower, and no layer of theirs
+    // has fewer than 12 and more than 3); with fewer tiles the implicit-GEMM kernels' reduction split keeps
+    // more compute units busy
     const bool pointwise_ok = allow_pointwise && pointwise_eligible(pl->args, x_align, 16, w_al16);
     int pw_a = 2, pw_b = 2;
     if (pointwise_ok) pointwise_tile(pl->args, &pw_a, &pw_b);
