@@ -234,10 +234,11 @@ __global__ __launch_bounds__(256) void depthwise3_vec_kernel(const ConvArgs p)
     }
 }
 
-template <int STRIDE, int VO>
-static hipError_t launch_dw3(const ConvArgs &a, hipStream_t stream)
+constexpr long long kDwSmallGrid = 256;
+
+template <int STRIDE, int VO, int RO>
+static hipError_t launch_dw3_rows(const ConvArgs &a, hipStream_t stream)
 {
-    constexpr int RO = (VO >= 8) ? 2 : (VO >= 4 ? 4 : 8);   // output rows per thread: narrow vectors (small maps) take more rows
     const long long items = (long long)a.N * a.C * ((a.Ho + RO - 1) / RO) * (a.Wo / VO);
     long long blocks = (items + 255) / 256;
     if (blocks > 1048576) blocks = 1048576;
@@ -247,6 +248,16 @@ static hipError_t launch_dw3(const ConvArgs &a, hipStream_t stream)
     b.fd_G = make_fastdiv((uint32_t)a.C);
     hipLaunchKernelGGL((depthwise3_vec_kernel<STRIDE, VO, RO>), dim3((unsigned)blocks), dim3(256), 0, stream, b);
     return hipGetLastError();
+}
+
+template <int STRIDE, int VO>
+static hipError_t launch_dw3(const ConvArgs &a, hipStream_t stream)
+{
+    constexpr int RO = (VO >= 8) ? 2 : (VO >= 4 ? 4 : 8);   // output rows per thread: narrow vectors (small maps) take more rows
+    // ... unless that leaves most compute units without a workgroup: then two rows per thread
+    const long long items = (long long)a.N * a.C * ((a.Ho + RO - 1) / RO) * (a.Wo / VO);
+    if (RO > 2 && items < 256 * kDwSmallGrid) return launch_dw3_rows<STRIDE, VO, 2>(a, stream);
+    return launch_dw3_rows<STRIDE, VO, RO>(a, stream);
 }
 
 hipError_t launch_depthwise(const ConvArgs &a, hipStream_t stream)
