@@ -304,3 +304,25 @@ def test_product_package_does_not_import_the_oracle():
                 assert "oracle" not in text.lower(), f
     with open(os.path.join(ROOT, "oracle", "__init__.py")) as fh:
         assert "paper_1901_00858_amd" not in fh.read().replace("never imports the product package", "")
+
+
+def test_instantiation_tables_are_joined_in_order(lib):
+    """The implicit-GEMM tables are compiled in parts and joined: same length for both weight layouts,
+    no instantiation twice, and the numbering that plans and remembered launch shapes refer to starts
+    with the throughput tile."""
+    for packed in (False, True):
+        names = []
+        while True:
+            n = hgc.igemm_variant_name(len(names), packed)
+            if not n:
+                break
+            names.append(n)
+        assert len(names) >= 90 and len(set(names)) == len(names)
+        assert names[0].startswith("igemm_kernel<3, 2, 4, 2, 4, 2, 4,"), names[0]
+        assert all(n.split(",")[8].strip() == ("true" if packed else "false") for n in names)
+        if packed:
+            count = len(names)
+        else:
+            first = names
+    assert count == len(first)
+    assert hgc.igemm_variant_name(10 ** 6, True) == ""
