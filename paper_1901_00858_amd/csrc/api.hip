@@ -396,7 +396,9 @@ static void make_plan(const Geometry &g0, bool with_ws, int x_align, bool w_al16
         // then the smallest halo patch
         ConvArgs *a = &pl->args;
         // 256 pixels per workgroup, 128 when that leaves most compute units without one
-        const int A = g.M > 32 ? 2 : 1;
+        // 64 output channels per workgroup unless that pads the channel count further than 32 would (M = 96: three
+        // workgroups of 32 instead of two of 64, and room for two of them per compute unit)
+        const int A = (g.M > 32 && ceil_div(g.M, 64) * 64 <= ceil_div(g.M, 32) * 32) ? 2 : 1;
         const int BN = (long long)ceil_div(g.M, 32 * A) * ceil_div((long long)g.Ho * g.Wo, 256) * g.N < kFirstSmallGrid ? 128 : 256;
         const int xv = (g.W % 2 == 0 && x_align % 4 == 0) ? 2 : 1;
         long long best_cost = -1;
