@@ -368,6 +368,26 @@ def test_first_layer_kernel_integer_exact_and_unaligned_input(oracle):
     assert_full(oracle, L, x, w, b, yd.cpu().numpy(), tag="first layer, unaligned x")
 
 
+def test_first_layer_kernel_caller_layout_with_unaligned_weights(oracle):
+    """Weights in the caller's layout at a 2-byte aligned address: the kernel gathers them with 2-byte loads."""
+    import torch
+    for t in ((1, 3, 40, 44, 64, 3, 1, 1), (1, 3, 51, 51, 48, 11, 4, 0)):
+        N, C, H, W, M, k, s_, p_ = t
+        L = ConvLayer("first", N, C, H, W, M, k, s_, p_, 1, 1, 1)
+        assert hgc.conv2d_plan(L, False, False).as_dict()["path"] == hgc.PATH_FIRST_LAYER
+        x, w, b = make_tensors(L, seed=9)
+        wbuf = torch.empty(w.size + 1, dtype=torch.float16, device="cuda")
+        wbuf[1:].copy_(torch.from_numpy(w.reshape(-1)))
+        xd, bd = torch.from_numpy(x).cuda(), torch.from_numpy(b).cuda()
+        yd = torch.empty(L.y_shape, dtype=torch.float16, device="cuda")
+        yd.view(torch.int16).fill_(0x7E00)
+        st = hgc.forward_raw(hgc.ConvDesc.make(L), xd.data_ptr(), wbuf[1:].data_ptr(), bd.data_ptr(), yd.data_ptr(),
+                             torch.cuda.current_stream().cuda_stream)
+        assert st == 0
+        torch.cuda.synchronize()
+        assert_full(oracle, L, x, w, b, yd.cpu().numpy(), tag="first layer, unaligned w")
+
+
 MULTI = [
     # N  C   H   W   M  k  s  p  G: small maps, image counts that do not fill the last tile
     (5, 64, 7, 7, 96, 3, 1, 1, 1),
