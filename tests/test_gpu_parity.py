@@ -254,7 +254,7 @@ def test_configs_batch1_full_tensor(oracle, cfg):
     assert worst <= 1.0
 
 
-@pytest.mark.parametrize("cfg,N", [("vgg16", 16), ("resnet50", 32), ("mobilenet_v1", 64)])
+@pytest.mark.parametrize("cfg,N", [("alexnet", 16), ("vgg16", 16), ("resnet50", 32), ("mobilenet_v1", 64)])
 def test_configs_full_batch_sampled(oracle, cfg, N):
     """Full-size tensors in the launch configuration the benchmark uses; outputs the
     oracle evaluates one by one: corners, edges, first and last image, random points."""
